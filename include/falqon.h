@@ -1,0 +1,164 @@
+/*
+ * falqon.h - C ABI of the MI355X (gfx950) melded FP8-LoRA linear layer.
+ *
+ * The layer is the hot path of FALQON (arXiv 2510.24061): an FP8 linear layer whose
+ * LoRA adapter is melded into the FP8-quantized backbone weight.  Four operations:
+ *
+ *   falqon_quantize      per-tensor FP8 quantizer Q_fp8
+ *   falqon_melded_fwd    quantize x, one FP8 product against the concatenated weight
+ *                        [W~ ; A~], split into the layer output and O_A = A x
+ *   falqon_melded_bwd    quantize dY, input gradient dX = dY~ W~, adapter gradient
+ *                        dB = dY~^T O_A, optional proxy-buffer step
+ *   falqon_proxy_update  row scores of the proxy buffer, top-k rows, requantize-and-
+ *                        write of those rows of W~
+ *
+ * Conventions (all calls)
+ *   - Orientation is row-major with tokens first: X[T,n], W~'[(m+r),n], Y[T,m],
+ *     O_A[T,r], dY[T,m], dX[T,n], dB[m,r], DeltaBuffer[m,r].  (The paper writes
+ *     activations as n x d columns, O = W x; T is its d.)
+ *   - Every pointer is a DEVICE pointer unless it is called "host".  Scales and amax
+ *     values are device scalars, so no call synchronises with the host.
+ *   - The caller owns every buffer.  The library allocates nothing and keeps no state
+ *     between calls.  `ws` is caller-provided scratch of at least
+ *     falqon_workspace_bytes() bytes; its contents are undefined after a call.
+ *   - Calls validate their arguments on the host first; on error nothing is launched.
+ *     Otherwise they enqueue kernels on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and return without waiting.
+ *   - Tensors are dense.  Pointers must be 16-byte aligned.  n, m and r must be
+ *     multiples of 16, r <= 256, T >= 1.
+ *   - FP8 codes are OCP E4M3 (max 448, no infinity) and OCP E5M2 (max 57344): the two
+ *     formats the paper fixes through their largest values.  Casts round to nearest,
+ *     ties to even, and saturate.  Non-finite inputs never fault; their outputs are
+ *     unspecified.
+ *   - Re-entrant for distinct buffers and streams.  Two calls that share an output
+ *     buffer or a workspace must be ordered by the caller.
+ */
+#ifndef FALQON_H
+#define FALQON_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FALQON_OK = 0,
+    FALQON_ERR_NULL = 1,       /* a required pointer is NULL */
+    FALQON_ERR_SHAPE = 2,      /* a size is out of range or not a multiple of 16 */
+    FALQON_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned */
+    FALQON_ERR_ENUM = 4,       /* unknown format or dtype */
+    FALQON_ERR_WORKSPACE = 5,  /* ws is NULL or smaller than falqon_workspace_bytes() */
+    FALQON_ERR_HIP = 6         /* a HIP launch failed */
+} falqon_status;
+
+typedef enum { FALQON_E4M3 = 0, FALQON_E5M2 = 1 } falqon_fmt;
+typedef enum { FALQON_BF16 = 0, FALQON_F32 = 1 } falqon_dtype;
+
+/* Human-readable name of a status code (host, static storage). */
+const char* falqon_status_string(falqon_status s);
+
+/*
+ * Scratch bytes any of the calls below needs for a layer of this shape (host function,
+ * no device access).  Returns 0 if the shape is invalid.
+ */
+size_t falqon_workspace_bytes(int64_t T, int64_t n, int64_t m, int64_t r);
+
+/*
+ * Per-tensor quantizer (quantization equation of "Low-precision floating-point
+ * quantization"; with scale_in it is the A-integration equation, which casts the
+ * adapter A with the backbone's scale).
+ *
+ *   amax = max |x|
+ *   s    = fmt_max / max(amax, 1e-12f)      (one fp32 division; the scale multiplies up
+ *                                            to the format's range and divides on rescale)
+ *   q    = cast_fmt( fl32(x * s) )          (one fp32 multiply, then the cast)
+ *
+ *   x          in   [rows, cols] of dtype xt, row stride ld_x elements
+ *   q          out  [rows, cols] FP8 codes, row stride ld_q bytes
+ *   scale_in   in   nullable.  NULL: derive s from amax.  Else use *scale_in as s.
+ *   scale_out  out  the scale used
+ *   amax_out   out  nullable; max |x|
+ * cols, ld_x and ld_q must be multiples of 16.  rows*cols = 0 is allowed (s = fmt_max/1e-12).
+ */
+falqon_status falqon_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t cols, int64_t ld_x,
+                              falqon_fmt fmt, const float* scale_in,
+                              uint8_t* q, int64_t ld_q, float* scale_out, float* amax_out,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Melded forward (forward loop of the gradient-computation algorithm; merged-output
+ * equation):
+ *
+ *   xq, s_x   = Q_E4M3(x)
+ *   O_merged  = xq . wq^T / (s_w * s_x)             [T, m+r], fp32 accumulation
+ *   y         = O_merged[:, :m]
+ *   o_a       = bf16( O_merged[:, m:] )             saved for the backward pass
+ *   amax_oa   = max |o_a|
+ *
+ *   x        in   bf16 [T, n]
+ *   wq       in   E4M3 [(m+r), n]: m backbone rows, then the r adapter rows cast with s_w
+ *   s_w      in   device scalar, the backbone's scale
+ *   xq, s_x  out  E4M3 [T, n] and its scale (the operands the product was formed from)
+ *   y        out  [T, m] of dtype yt
+ *   o_a      out  bf16 [T, r]
+ *   amax_oa  out  device scalar
+ */
+falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s_w,
+                                int64_t T, int64_t n, int64_t m, int64_t r,
+                                uint8_t* xq, float* s_x, void* y, falqon_dtype yt,
+                                void* o_a, float* amax_oa,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Melded backward (first two lines of the backward-and-update loop, plus the input
+ * gradient that an FP8 linear layer owes its predecessor; gradients are E5M2):
+ *
+ *   dyq, s_dy = Q_E5M2(dy)
+ *   dx        = dyq . wq[:m] / (s_dy * s_w)          only the backbone rows take part
+ *   s_oa      = 448 / max(amax_oa, 1e-12f);  oaq = cast_E4M3( fl32(o_a * s_oa) )
+ *   d_b       = dyq^T . oaq / (s_dy * s_oa)          modified LoRA-backward equation
+ *   delta_buf += -lr * d_b                           if delta_buf != NULL (plain SGD as
+ *                                                    the optimizer that fills the buffer)
+ *
+ *   dy         in   bf16 [T, m]
+ *   o_a, amax_oa in bf16 [T, r] and device scalar, as falqon_melded_fwd produced them
+ *   dyq, s_dy  out  E5M2 [T, m] and its scale
+ *   dx         out  [T, n] of dtype dxt
+ *   d_b        out  fp32 [m, r]
+ *   delta_buf  i/o  nullable fp32 [m, r]
+ */
+falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* s_w,
+                                const void* o_a, const float* amax_oa,
+                                int64_t T, int64_t n, int64_t m, int64_t r,
+                                uint8_t* dyq, float* s_dy, void* dx, falqon_dtype dxt,
+                                float* d_b, float* delta_buf, float lr,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Row-wise proxy update (update equation; last two lines of the backward-and-update loop):
+ *
+ *   score_i = sum_p |delta_buf[i,p]|                 fp64, p ascending
+ *   idx     = the k rows of largest score, larger first, ties by smaller row index
+ *   for i in idx, all j:
+ *       acc = value(wq[i,j]);  for p ascending: acc += delta_buf[i,p] * value(wq[m+p,j])   (fp64)
+ *       wq[i,j] = cast_E4M3( (float)acc )
+ *   if clear_selected: delta_buf[i,:] = +0 for i in idx
+ *
+ * The adapter is the one stored in rows [m, m+r) of wq, so both terms carry the scale
+ * s_w, which cancels and stays fixed.  Rows outside idx and the adapter rows are not
+ * written.  1 <= k <= m, m <= 65536.
+ *
+ *   delta_buf  i/o  fp32 [m, r]
+ *   wq         i/o  E4M3 [(m+r), n]
+ *   idx_out    out  int32 [k], device
+ */
+falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
+                                  int32_t* idx_out, int clear_selected,
+                                  void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FALQON_H */

@@ -1,0 +1,179 @@
+"""ctypes binding of libfalqon.so: argument marshalling only.
+
+Every function takes torch tensors that already live on the GPU, passes their device
+pointers and the current HIP stream through the C ABI (include/falqon.h) and returns.
+Nothing is computed here, and there is no fallback: if the library is missing or a call
+fails, an exception is raised.
+"""
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+E4M3, E5M2 = 0, 1
+BF16, F32 = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfalqon.so")
+_lib = None
+
+
+class FalqonError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: falqon status {status} ({status_string(status)})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Load libfalqon.so (built in-tree by paper_2510_24061_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2510_24061_amd.build`")
+        L = ctypes.CDLL(_LIB_PATH)
+        c = ctypes
+        vp, i64, f32p = c.c_void_p, c.c_int64, c.c_void_p
+        L.falqon_status_string.restype = c.c_char_p
+        L.falqon_status_string.argtypes = [c.c_int]
+        L.falqon_workspace_bytes.restype = c.c_size_t
+        L.falqon_workspace_bytes.argtypes = [i64, i64, i64, i64]
+        L.falqon_quantize.restype = c.c_int
+        L.falqon_quantize.argtypes = [vp, c.c_int, i64, i64, i64, c.c_int, f32p, vp, i64, f32p, f32p,
+                                      vp, c.c_size_t, vp]
+        L.falqon_melded_fwd.restype = c.c_int
+        L.falqon_melded_fwd.argtypes = [vp, vp, f32p, i64, i64, i64, i64, vp, f32p, vp, c.c_int, vp, f32p,
+                                        vp, c.c_size_t, vp]
+        L.falqon_melded_bwd.restype = c.c_int
+        L.falqon_melded_bwd.argtypes = [vp, vp, f32p, vp, f32p, i64, i64, i64, i64, vp, f32p, vp, c.c_int,
+                                        f32p, f32p, c.c_float, vp, c.c_size_t, vp]
+        L.falqon_proxy_update.restype = c.c_int
+        L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().falqon_status_string(int(status)).decode()
+
+
+def workspace_bytes(T: int, n: int, m: int, r: int) -> int:
+    return int(lib().falqon_workspace_bytes(T, n, m, r))
+
+
+def _p(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float32:
+        return F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise FalqonError(status, where)
+
+
+def _dev(*tensors):
+    for t in tensors:
+        if t is not None and not (t.is_cuda and t.is_contiguous()):
+            raise ValueError("tensors must be contiguous GPU tensors")
+
+
+def quantize(x: torch.Tensor, fmt: int, q: torch.Tensor, scale_out: torch.Tensor,
+             ws: torch.Tensor, scale_in: Optional[torch.Tensor] = None,
+             amax_out: Optional[torch.Tensor] = None) -> None:
+    """falqon_quantize on a dense 2-D (or flat) tensor."""
+    _dev(x, q, scale_out, ws, scale_in, amax_out)
+    rows, cols = (x.shape if x.dim() == 2 else (1, x.numel()))
+    st = lib().falqon_quantize(_p(x), _dtype_code(x), rows, cols, cols, fmt, _p(scale_in), _p(q), cols,
+                               _p(scale_out), _p(amax_out), _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_quantize")
+
+
+def melded_fwd(x, wq, s_w, m: int, r: int, xq, s_x, y, o_a, amax_oa, ws) -> None:
+    _dev(x, wq, s_w, xq, s_x, y, o_a, amax_oa, ws)
+    T, n = x.shape
+    st = lib().falqon_melded_fwd(_p(x), _p(wq), _p(s_w), T, n, m, r, _p(xq), _p(s_x), _p(y), _dtype_code(y),
+                                 _p(o_a), _p(amax_oa), _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_melded_fwd")
+
+
+def melded_bwd(dy, wq, s_w, o_a, amax_oa, n: int, r: int, dyq, s_dy, dx, d_b, delta_buf, lr: float, ws) -> None:
+    _dev(dy, wq, s_w, o_a, amax_oa, dyq, s_dy, dx, d_b, delta_buf, ws)
+    T, m = dy.shape
+    st = lib().falqon_melded_bwd(_p(dy), _p(wq), _p(s_w), _p(o_a), _p(amax_oa), T, n, m, r, _p(dyq), _p(s_dy),
+                                 _p(dx), _dtype_code(dx), _p(d_b), _p(delta_buf), float(lr),
+                                 _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_melded_bwd")
+
+
+def proxy_update(delta_buf, wq, m: int, r: int, k: int, idx_out, ws, clear_selected: bool = True) -> None:
+    _dev(delta_buf, wq, idx_out, ws)
+    n = wq.shape[1]
+    st = lib().falqon_proxy_update(_p(delta_buf), _p(wq), n, m, r, k, _p(idx_out), 1 if clear_selected else 0,
+                                   _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_proxy_update")
+
+
+class MeldedLinear:
+    """Buffers of one melded layer plus the four calls, for tests and the benchmark.
+
+    State kept between steps: wq = [W~ ; A~] (E4M3, [(m+r), n]), s_w, delta_buf (fp32 [m, r]).
+    Everything else is per-step output or scratch.  All memory is allocated once here.
+    """
+
+    def __init__(self, T: int, n: int, m: int, r: int, k: int, out_dtype=torch.bfloat16, device="cuda"):
+        self.T, self.n, self.m, self.r, self.k = T, n, m, r, k
+        dev = torch.device(device)
+        u8, f32 = torch.uint8, torch.float32
+        self.wq = torch.zeros(m + r, n, dtype=u8, device=dev)
+        self.s_w = torch.zeros(1, dtype=f32, device=dev)
+        self.delta_buf = torch.zeros(m, r, dtype=f32, device=dev)
+        self.xq = torch.empty(T, n, dtype=u8, device=dev)
+        self.s_x = torch.zeros(1, dtype=f32, device=dev)
+        self.y = torch.empty(T, m, dtype=out_dtype, device=dev)
+        self.o_a = torch.empty(T, r, dtype=torch.bfloat16, device=dev)
+        self.amax_oa = torch.zeros(1, dtype=f32, device=dev)
+        self.dyq = torch.empty(T, m, dtype=u8, device=dev)
+        self.s_dy = torch.zeros(1, dtype=f32, device=dev)
+        self.dx = torch.empty(T, n, dtype=out_dtype, device=dev)
+        self.d_b = torch.empty(m, r, dtype=f32, device=dev)
+        self.idx = torch.zeros(k, dtype=torch.int32, device=dev)
+        nbytes = workspace_bytes(T, n, m, r)
+        if nbytes == 0:
+            raise ValueError("invalid layer shape")
+        self.ws = torch.empty(nbytes, dtype=u8, device=dev)
+
+    def init_weights(self, w: torch.Tensor, a: torch.Tensor) -> None:
+        """Initialization steps that need no SVD: W~, s_w <- Q(W); A~ <- cast(A * s_w); buffer <- 0."""
+        s_tmp = torch.zeros(1, dtype=torch.float32, device=self.wq.device)
+        quantize(w.contiguous(), E4M3, self.wq[: self.m], self.s_w, self.ws)
+        quantize(a.contiguous(), E4M3, self.wq[self.m:], s_tmp, self.ws, scale_in=self.s_w)
+        self.delta_buf.zero_()
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        melded_fwd(x, self.wq, self.s_w, self.m, self.r, self.xq, self.s_x, self.y, self.o_a, self.amax_oa, self.ws)
+        return self.y
+
+    def backward(self, dy: torch.Tensor, lr: float = 2e-4, accumulate: bool = True) -> torch.Tensor:
+        melded_bwd(dy, self.wq, self.s_w, self.o_a, self.amax_oa, self.n, self.r, self.dyq, self.s_dy, self.dx,
+                   self.d_b, self.delta_buf if accumulate else None, lr, self.ws)
+        return self.dx
+
+    def update(self, clear_selected: bool = True) -> torch.Tensor:
+        proxy_update(self.delta_buf, self.wq, self.m, self.r, self.k, self.idx, self.ws, clear_selected)
+        return self.idx

@@ -1,0 +1,230 @@
+// Adapter gradient in its reformulated shape, dL/dB = dL/dO (A x)^T (modified
+// LoRA-backward equation; first line of the backward-and-update loop):
+//
+//   dB[i,p] = ( sum_t value5(dyq[t,i]) * value4(oaq[t,p]) ) / (s_dy * s_oa)
+//
+// dyq is the E5M2 gradient that the input-gradient GEMM already uses; oaq is the saved
+// O_A = A x (bf16) cast to E4M3 inside this kernel's load stage with
+// s_oa = 448 / max(amax_oa, 1e-12f), so no separate small-matrix quantize pass exists.
+//
+// The contraction runs over tokens, the strided dimension of both operands.  Both tiles are
+// therefore kept as [token][feature] in LDS and read with ds_read_b64_tr_b8, which returns
+// eight consecutive tokens of one feature per lane: the matrix-core operand layout.
+// The kernel is bound by the single read of dyq, so tokens are split over many workgroups;
+// each split writes an fp32 partial and a second pass adds the partials in a fixed order
+// (bitwise reproducible, no floating-point atomics) and applies the proxy-buffer step.
+#include "falqon_internal.h"
+
+namespace falqon {
+namespace {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef int v2i __attribute__((ext_vector_type(2)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+#define FQ_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
+#define FQ_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+__device__ __attribute__((aligned(16))) uint8_t g_zero16[16];
+
+constexpr int BI = 128;    // rows of dB (output features) per workgroup
+constexpr int BP = 64;     // columns of dB (rank) per workgroup
+constexpr int BT = 128;    // tokens per step
+constexpr int kThreads = 256;
+
+// [token][feature] tile with CH 16-byte chunks per token row; chunk c of row t sits at c ^ swz.
+template <int CH>
+__device__ __forceinline__ int swz_t(int trow) { return trow & (CH - 1); }
+
+// Eight consecutive tokens of one feature per lane; four reads make a 32-token operand.
+// Lane s of a 16-lane group supplies the address of token row (s % 16) / 2, feature block
+// 8 * (s % 2); lane L then receives feature (L % 16) of the group's 16-feature span.
+template <int CH>
+__device__ __forceinline__ v8i read_tokens_of_feature(const uint8_t* tile, int feat_base, int kh, int lane)
+{
+    v8i r;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int trow = kh * 64 + (lane >> 5) * 32 + t * 8 + ((lane & 15) >> 1);
+        const int feat = feat_base + ((lane >> 4) & 1) * 16 + (lane & 1) * 8;
+        const uint8_t* p = tile + trow * (CH * 16) + ((((feat >> 4) ^ swz_t<CH>(trow)) << 4) | (feat & 15));
+        const v2i d = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(p));
+        r[2 * t] = d[0];
+        r[2 * t + 1] = d[1];
+    }
+    return r;
+}
+
+__device__ __forceinline__ uint32_t cast4_e4m3(float a, float b, float c, float d)
+{
+    a = __builtin_amdgcn_fmed3f(a, -448.0f, 448.0f);
+    b = __builtin_amdgcn_fmed3f(b, -448.0f, 448.0f);
+    c = __builtin_amdgcn_fmed3f(c, -448.0f, 448.0f);
+    d = __builtin_amdgcn_fmed3f(d, -448.0f, 448.0f);
+    int w = 0;
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, w, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, w, true);
+    return static_cast<uint32_t>(w);
+}
+
+// grid: (ceil(m / BI), splits, ceil(r / BP)); partial[split][m][r]
+__global__ void __launch_bounds__(kThreads)
+db_partial_kernel(const uint8_t* __restrict__ dyq, const uint16_t* __restrict__ o_a,
+                  const float* __restrict__ amax_oa, int64_t T, int64_t m, int64_t r,
+                  int64_t tokens_per_split, float* __restrict__ partial)
+{
+    constexpr int CH_DY = BI / 16, CH_OA = BP / 16;
+    __shared__ __attribute__((aligned(1024))) uint8_t s_dy[BT * BI];   // [token][feature i]
+    __shared__ __attribute__((aligned(1024))) uint8_t s_oa[BT * BP];   // [token][rank p]
+
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t i0 = static_cast<int64_t>(blockIdx.x) * BI;
+    const int64_t p0 = static_cast<int64_t>(blockIdx.z) * BP;
+    const int64_t t_begin = static_cast<int64_t>(blockIdx.y) * tokens_per_split;
+    int64_t t_end = t_begin + tokens_per_split;
+    if (t_end > T) t_end = T;
+    const float s_oa_scale = 448.0f / fmaxf(*amax_oa, 1e-12f);
+
+    v16f acc[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
+
+    for (int64_t t0 = t_begin; t0 < t_end; t0 += BT) {
+        __syncthreads();                       // the previous step's operand reads are done
+        // dyq tile: BT rows x BI bytes = 16 KB = 16 wave instructions of 1 KB (8 token rows each)
+#pragma unroll
+        for (int it = 0; it < BT * BI / 1024 / 4; ++it) {
+            const int q = it * 4 + wave;
+            const int trow = q * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ swz_t<CH_DY>(trow);
+            const int64_t gt = t0 + trow, gi = i0 + c * 16;
+            const uint8_t* src = (gt < t_end && gi < m) ? dyq + gt * m + gi : g_zero16;
+            __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(s_dy + q * 1024), 16, 0, 0);
+        }
+        // O_A tile: BT rows x BP bf16 -> E4M3 bytes.  256 threads x 32 values: thread -> (row, half row)
+        {
+            const int trow = threadIdx.x >> 1, half = threadIdx.x & 1;     // 32 ranks per half
+            const int64_t gt = t0 + trow;
+            uint32_t codes[8];
+#pragma unroll
+            for (int c4 = 0; c4 < 8; ++c4) codes[c4] = 0u;
+            if (gt < t_end) {
+#pragma unroll
+                for (int v8 = 0; v8 < 4; ++v8) {                           // 8 bf16 per 16-byte load
+                    const int64_t gp = p0 + half * 32 + v8 * 8;
+                    if (gp < r) {
+                        const uint4 w = *reinterpret_cast<const uint4*>(o_a + gt * r + gp);
+                        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+                        float f[8];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            f[2 * e] = __fmul_rn(__uint_as_float(ww[e] << 16), s_oa_scale);
+                            f[2 * e + 1] = __fmul_rn(__uint_as_float(ww[e] & 0xffff0000u), s_oa_scale);
+                        }
+                        codes[2 * v8] = cast4_e4m3(f[0], f[1], f[2], f[3]);
+                        codes[2 * v8 + 1] = cast4_e4m3(f[4], f[5], f[6], f[7]);
+                    }
+                }
+            }
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {                                   // two 16-byte chunks
+                const int chunk = (half * 2 + c) ^ swz_t<CH_OA>(trow);
+                uint4 o;
+                o.x = codes[4 * c]; o.y = codes[4 * c + 1]; o.z = codes[4 * c + 2]; o.w = codes[4 * c + 3];
+                *reinterpret_cast<uint4*>(s_oa + trow * BP + chunk * 16) = o;
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        // wave w owns features [32 w, 32 w + 32) of the tile and both 32-wide rank blocks
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+            const v8i a = read_tokens_of_feature<CH_DY>(s_dy, wave * 32, kh, lane);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const v8i bb = read_tokens_of_feature<CH_OA>(s_oa, b * 32, kh, lane);
+                acc[b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bb, acc[b], 1 /* E5M2 */, 0 /* E4M3 */,
+                                                                          0, 0, 0, 0);
+            }
+        }
+    }
+
+    float* out = partial + static_cast<int64_t>(blockIdx.y) * m * r;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const int64_t p = p0 + b * 32 + (lane & 31);
+        if (p >= r) continue;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t i = i0 + wave * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+            if (i < m) out[i * r + p] = acc[b][v];
+        }
+    }
+}
+
+// dB = (sum of partials, split ascending) / (s_dy * s_oa);  delta_buf += -lr * dB
+__global__ void __launch_bounds__(kThreads)
+db_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count,
+                 const float* __restrict__ s_dy, const float* __restrict__ amax_oa,
+                 float* __restrict__ d_b, float* delta_buf, float lr)
+{
+    const float s_oa_scale = 448.0f / fmaxf(*amax_oa, 1e-12f);
+    const float inv = 1.0f / ((*s_dy) * s_oa_scale);
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * 4;
+    for (int64_t e = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4; e < count; e += stride) {
+        float4 s = *reinterpret_cast<const float4*>(partial + e);
+        for (int sp = 1; sp < splits; ++sp) {
+            const float4 v = *reinterpret_cast<const float4*>(partial + sp * count + e);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
+        *reinterpret_cast<float4*>(d_b + e) = s;
+        if (delta_buf) {
+            float4 d = *reinterpret_cast<const float4*>(delta_buf + e);
+            d.x = __fadd_rn(d.x, __fmul_rn(-lr, s.x));
+            d.y = __fadd_rn(d.y, __fmul_rn(-lr, s.y));
+            d.z = __fadd_rn(d.z, __fmul_rn(-lr, s.z));
+            d.w = __fadd_rn(d.w, __fmul_rn(-lr, s.w));
+            *reinterpret_cast<float4*>(delta_buf + e) = d;
+        }
+    }
+}
+
+}  // namespace
+
+int db_splits(int64_t T, int64_t m)
+{
+    const int64_t i_tiles = (m + BI - 1) / BI;
+    int64_t splits = (512 + i_tiles - 1) / i_tiles;          // aim at ~2 workgroups per CU
+    const int64_t max_by_tokens = (T + BT - 1) / BT;
+    if (splits > max_by_tokens) splits = max_by_tokens;
+    if (splits > kDbSplitMax) splits = kDbSplitMax;
+    if (splits < 1) splits = 1;
+    return static_cast<int>(splits);
+}
+
+hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, const float* amax_oa,
+                     int64_t T, int64_t m, int64_t r, float* d_b, float* delta_buf, float lr,
+                     float* partials, int splits, hipStream_t stream)
+{
+    // tokens per split: a multiple of the step so that every split starts on a tile boundary
+    int64_t tps = (T + splits - 1) / splits;
+    tps = (tps + BT - 1) / BT * BT;
+    const dim3 grid(static_cast<unsigned>((m + BI - 1) / BI), static_cast<unsigned>(splits),
+                    static_cast<unsigned>((r + BP - 1) / BP));
+    db_partial_kernel<<<grid, kThreads, 0, stream>>>(dyq, static_cast<const uint16_t*>(o_a), amax_oa, T, m, r, tps,
+                                                     partials);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int64_t count = m * r;
+    int64_t blocks = (count / 4 + kThreads - 1) / kThreads;
+    if (blocks > 1024) blocks = 1024;
+    if (blocks < 1) blocks = 1;
+    db_reduce_kernel<<<static_cast<unsigned>(blocks), kThreads, 0, stream>>>(partials, splits, count, s_dy, amax_oa,
+                                                                             d_b, delta_buf, lr);
+    return hipGetLastError();
+}
+
+}  // namespace falqon

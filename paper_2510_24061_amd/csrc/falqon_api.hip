@@ -1,0 +1,179 @@
+// C ABI of libfalqon: argument validation on the host, then kernel launches on the caller's
+// stream.  Nothing here allocates, synchronises or keeps state.
+#include "falqon_internal.h"
+
+namespace falqon {
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+WsLayout ws_layout(int64_t T, int64_t n, int64_t m, int64_t r)
+{
+    (void)n;
+    WsLayout w;
+    size_t off = 0;
+    w.amax_partials = off; off = align_up(off + sizeof(float) * kMaxAmaxBlocks, 256);
+    w.scores = off;        off = align_up(off + sizeof(double) * static_cast<size_t>(m), 256);
+    w.db_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(db_splits(T, m)) *
+                                                    static_cast<size_t>(m) * static_cast<size_t>(r), 256);
+    w.total = off;
+    return w;
+}
+
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+static bool bad_layer_shape(int64_t T, int64_t n, int64_t m, int64_t r)
+{
+    return T < 1 || n < 16 || m < 16 || r < 16 || (n % 16) || (m % 16) || (r % 16) || r > 256 ||
+           T > (int64_t(1) << 24) || n > (int64_t(1) << 20) || m > (int64_t(1) << 20);
+}
+
+}  // namespace falqon
+
+using namespace falqon;
+
+extern "C" {
+
+const char* falqon_status_string(falqon_status s)
+{
+    switch (s) {
+        case FALQON_OK: return "ok";
+        case FALQON_ERR_NULL: return "null pointer";
+        case FALQON_ERR_SHAPE: return "bad shape";
+        case FALQON_ERR_ALIGN: return "pointer not 16-byte aligned";
+        case FALQON_ERR_ENUM: return "unknown format or dtype";
+        case FALQON_ERR_WORKSPACE: return "workspace missing or too small";
+        case FALQON_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+size_t falqon_workspace_bytes(int64_t T, int64_t n, int64_t m, int64_t r)
+{
+    if (bad_layer_shape(T, n, m, r)) return 0;
+    return ws_layout(T, n, m, r).total;
+}
+
+falqon_status falqon_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t cols, int64_t ld_x,
+                              falqon_fmt fmt, const float* scale_in,
+                              uint8_t* q, int64_t ld_q, float* scale_out, float* amax_out,
+                              void* ws, size_t ws_bytes, void* stream)
+{
+    if (xt != FALQON_BF16 && xt != FALQON_F32) return FALQON_ERR_ENUM;
+    if (fmt != FALQON_E4M3 && fmt != FALQON_E5M2) return FALQON_ERR_ENUM;
+    if (rows < 0 || cols < 0 || (cols % 16) || ld_x < cols || ld_q < cols || (ld_x % 16) || (ld_q % 16))
+        return FALQON_ERR_SHAPE;
+    if (rows > (int64_t(1) << 40) / (cols > 0 ? cols : 1)) return FALQON_ERR_SHAPE;
+    const bool empty = rows == 0 || cols == 0;
+    if (!scale_out || (!empty && (!x || !q))) return FALQON_ERR_NULL;
+    if (!empty && (misaligned(x) || misaligned(q))) return FALQON_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(scale_out) & 3u) || (amax_out && (reinterpret_cast<uintptr_t>(amax_out) & 3u)) ||
+        (scale_in && (reinterpret_cast<uintptr_t>(scale_in) & 3u)))
+        return FALQON_ERR_ALIGN;
+    if (!ws || ws_bytes < sizeof(float) * kMaxAmaxBlocks) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    hipError_t e = launch_quantize(x, xt, empty ? 0 : rows, cols > 0 ? cols : 16, ld_x, fmt, scale_in, q, ld_q,
+                                   scale_out, amax_out, static_cast<float*>(ws), nullptr,
+                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s_w,
+                                int64_t T, int64_t n, int64_t m, int64_t r,
+                                uint8_t* xq, float* s_x, void* y, falqon_dtype yt,
+                                void* o_a, float* amax_oa,
+                                void* ws, size_t ws_bytes, void* stream)
+{
+    if (yt != FALQON_BF16 && yt != FALQON_F32) return FALQON_ERR_ENUM;
+    if (bad_layer_shape(T, n, m, r)) return FALQON_ERR_SHAPE;
+    if (!x || !wq || !s_w || !xq || !s_x || !y || !o_a || !amax_oa) return FALQON_ERR_NULL;
+    if (misaligned(x) || misaligned(wq) || misaligned(xq) || misaligned(y) || misaligned(o_a))
+        return FALQON_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(s_w) & 3u) || (reinterpret_cast<uintptr_t>(s_x) & 3u) ||
+        (reinterpret_cast<uintptr_t>(amax_oa) & 3u))
+        return FALQON_ERR_ALIGN;
+    const WsLayout L = ws_layout(T, n, m, r);
+    if (!ws || ws_bytes < L.total) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* w8 = static_cast<uint8_t*>(ws);
+
+    // x~, s_x <- Q_E4M3(x); the cast pass also resets the running maximum of O_A
+    hipError_t e = launch_quantize(x, FALQON_BF16, T, n, n, FALQON_E4M3, nullptr, xq, n, s_x, nullptr,
+                                   reinterpret_cast<float*>(w8 + L.amax_partials),
+                                   reinterpret_cast<uint32_t*>(amax_oa), st);
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+
+    // O_merged <- x~ W~'^T / (s_w s_x), split into y and O_A
+    GemmArgs g;
+    g.a = xq; g.lda = n; g.a_fmt = 0;
+    g.b = wq; g.ldb = n; g.b_is_kn = 0;
+    g.M = T; g.N = m + r; g.K = n;
+    g.sa = s_x; g.sb = s_w;
+    g.c0 = y; g.ldc0 = m; g.c0_is_f32 = (yt == FALQON_F32); g.n_split = m;
+    g.c1 = o_a; g.ldc1 = r; g.amax1 = reinterpret_cast<uint32_t*>(amax_oa);
+    e = launch_gemm(g, st);
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* s_w,
+                                const void* o_a, const float* amax_oa,
+                                int64_t T, int64_t n, int64_t m, int64_t r,
+                                uint8_t* dyq, float* s_dy, void* dx, falqon_dtype dxt,
+                                float* d_b, float* delta_buf, float lr,
+                                void* ws, size_t ws_bytes, void* stream)
+{
+    if (dxt != FALQON_BF16 && dxt != FALQON_F32) return FALQON_ERR_ENUM;
+    if (bad_layer_shape(T, n, m, r)) return FALQON_ERR_SHAPE;
+    if (!dy || !wq || !s_w || !o_a || !amax_oa || !dyq || !s_dy || !dx || !d_b) return FALQON_ERR_NULL;
+    if (misaligned(dy) || misaligned(wq) || misaligned(o_a) || misaligned(dyq) || misaligned(dx) ||
+        misaligned(d_b) || (delta_buf && misaligned(delta_buf)))
+        return FALQON_ERR_ALIGN;
+    if ((reinterpret_cast<uintptr_t>(s_w) & 3u) || (reinterpret_cast<uintptr_t>(s_dy) & 3u) ||
+        (reinterpret_cast<uintptr_t>(amax_oa) & 3u))
+        return FALQON_ERR_ALIGN;
+    const WsLayout L = ws_layout(T, n, m, r);
+    if (!ws || ws_bytes < L.total) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* w8 = static_cast<uint8_t*>(ws);
+
+    // dy~, s_dy <- Q_E5M2(dy)
+    hipError_t e = launch_quantize(dy, FALQON_BF16, T, m, m, FALQON_E5M2, nullptr, dyq, m, s_dy, nullptr,
+                                   reinterpret_cast<float*>(w8 + L.amax_partials), nullptr, st);
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+
+    // dX <- dy~ W~ / (s_dy s_w): the backbone rows of the concatenated weight, read as [K = m, N = n]
+    GemmArgs g;
+    g.a = dyq; g.lda = m; g.a_fmt = 1;
+    g.b = wq; g.ldb = n; g.b_is_kn = 1;
+    g.M = T; g.N = n; g.K = m;
+    g.sa = s_dy; g.sb = s_w;
+    g.c0 = dx; g.ldc0 = n; g.c0_is_f32 = (dxt == FALQON_F32); g.n_split = n;
+    g.c1 = nullptr; g.ldc1 = 0; g.amax1 = nullptr;
+    e = launch_gemm(g, st);
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+
+    // dB <- dy~^T O_A~ / (s_dy s_oa);  DeltaBuffer += -lr dB
+    e = launch_db(dyq, s_dy, o_a, amax_oa, T, m, r, d_b, delta_buf, lr,
+                  reinterpret_cast<float*>(w8 + L.db_partials), db_splits(T, m), st);
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
+                                  int32_t* idx_out, int clear_selected,
+                                  void* ws, size_t ws_bytes, void* stream)
+{
+    if (bad_layer_shape(1, n, m, r) || m > 65536 || k < 1 || k > m) return FALQON_ERR_SHAPE;
+    if (!delta_buf || !wq || !idx_out) return FALQON_ERR_NULL;
+    if (misaligned(delta_buf) || misaligned(wq) || (reinterpret_cast<uintptr_t>(idx_out) & 3u))
+        return FALQON_ERR_ALIGN;
+    const WsLayout L = ws_layout(1, n, m, r);
+    if (!ws || ws_bytes < L.scores + sizeof(double) * static_cast<size_t>(m)) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    uint8_t* w8 = static_cast<uint8_t*>(ws);
+    hipError_t e = launch_proxy_update(delta_buf, wq, n, m, r, k, idx_out, clear_selected,
+                                       reinterpret_cast<double*>(w8 + L.scores), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal declarations shared by the translation units of libfalqon (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "falqon.h"
+
+namespace falqon {
+
+// ---- workspace -------------------------------------------------------------------------
+// One layout serves all four calls; the regions never overlap so a forward, a backward
+// and an update of the same layer may share one workspace when run in stream order.
+constexpr int kMaxAmaxBlocks = 1024;   // per-block partial maxima written by the amax pass
+constexpr int kDbSplitMax = 32;        // upper bound on the token splits of the dB contraction
+
+struct WsLayout {
+    size_t amax_partials;   // float[kMaxAmaxBlocks]
+    size_t scores;          // double[m]
+    size_t db_partials;     // float[splits][m][r]
+    size_t total;
+};
+WsLayout ws_layout(int64_t T, int64_t n, int64_t m, int64_t r);
+int db_splits(int64_t T, int64_t m);
+
+// ---- quantizer (quantize.hip) ------------------------------------------------------------
+// Two launches: per-block partial maxima, then scale + cast.  `zero_word` (nullable) is a
+// device word the cast pass clears, used to reset the running maximum of O_A.
+hipError_t launch_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t cols, int64_t ld_x,
+                           falqon_fmt fmt, const float* scale_in, uint8_t* q, int64_t ld_q,
+                           float* scale_out, float* amax_out, float* partials, uint32_t* zero_word,
+                           hipStream_t stream);
+
+// ---- FP8 GEMMs (gemm.hip) ----------------------------------------------------------------
+// C[M,N] = A[M,K] . op(B) * 1 / (sa * sb), fp32 accumulation on the FP8 matrix cores.
+//   b_is_kn = 0: B is [N,K] (K contiguous)  - forward, against the concatenated weight
+//   b_is_kn = 1: B is [K,N] (N contiguous)  - input gradient, against the backbone rows
+// Columns [0, n_split) go to c0 (ldc0), columns [n_split, N) go to c1 as bf16 (ldc1) and
+// their running absolute maximum (after bf16 rounding) is folded into *amax1.
+struct GemmArgs {
+    const uint8_t* a; int64_t lda; int a_fmt;      // a_fmt: 0 = E4M3, 1 = E5M2
+    const uint8_t* b; int64_t ldb; int b_is_kn;    // B is always E4M3
+    int64_t M, N, K;
+    const float* sa; const float* sb;              // device scalars
+    void* c0; int64_t ldc0; int c0_is_f32; int64_t n_split;
+    void* c1; int64_t ldc1; uint32_t* amax1;
+};
+hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
+
+// ---- adapter gradient (db.hip) -------------------------------------------------------------
+hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, const float* amax_oa,
+                     int64_t T, int64_t m, int64_t r, float* d_b, float* delta_buf, float lr,
+                     float* partials, int splits, hipStream_t stream);
+
+// ---- proxy update (proxy.hip) ----------------------------------------------------------------
+hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
+                               int32_t* idx_out, int clear_selected, double* scores, hipStream_t stream);
+
+}  // namespace falqon

@@ -1,0 +1,268 @@
+"""GPU parity of the melded forward, backward and proxy update against the CPU oracle.
+
+Bars: FP8 codes, scales and selected row indices bit-exact; GEMM outputs within relative
+Frobenius error 1e-3 of the oracle applied to the same FP8 operands (fp32 output against the
+fp64 oracle, bf16 output against the oracle rounded to bf16).  Inputs of each call come from
+the seeded generator or from the oracle, never from another GPU call.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_24061_amd as fq
+import workloads
+from gpu_common import layer_on_gpu, np_of, oracle_weights, relf, sample_indices
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+
+SHAPES = [
+    # T, n, m, r, k, outliers
+    (256, 512, 512, 16, 8, False),        # config 1
+    (200, 384, 208, 16, 5, False),        # ragged in every dimension, several small tiles
+    (1, 128, 16, 16, 1, False),           # a single token, smallest legal sizes
+    (300, 1024, 1040, 64, 32, True),      # m + r = 1104: four and a bit 256-wide tiles
+    (520, 272, 528, 32, 16, True),        # K tails: n = 272 and m = 528 are not multiples of 128
+    (2100, 1024, 4112, 48, 12, True),     # enough tiles for the 256x256 path, ragged tails
+]
+
+
+def _inputs(T, n, m, r, outliers, seed):
+    d = workloads.make_inputs(T, n, m, r, seed, outliers)
+    wcat, s_w = oracle_weights(d["w"], d["a"])
+    return d, wcat, s_w
+
+
+def _check_forward(T, n, m, r, k, d, wcat, s_w, out_dtype, n_sample=96):
+    """Sampled rows x all columns and all rows x sampled columns (all of them when small);
+    O_A is always checked in full because its maximum is an output."""
+    layer = layer_on_gpu(T, n, m, r, k, wcat, s_w, out_dtype)
+    layer.forward(d["x"].cuda())
+    torch.cuda.synchronize()
+    x = d["x"].float().numpy()
+    xq_ref, s_x_ref, _ = oracle.quantize(x, oracle.E4M3)
+    assert np.array_equal(np_of(layer.xq), xq_ref)
+    assert np.float32(layer.s_x.item()).tobytes() == s_x_ref.tobytes()
+    y = np_of(layer.y)
+    rnd = (lambda v: v) if out_dtype == torch.float32 else oracle.round_bf16
+    rows = sample_indices(T, n_sample, seed=T)
+    cols = sample_indices(m, n_sample, seed=m)
+    by_rows = oracle.melded_fwd(xq_ref, wcat, s_w, s_x_ref, m, r, rows=rows)          # [rows, m + r]
+    by_cols = oracle.melded_fwd(xq_ref, wcat, s_w, s_x_ref, m, r, cols=np.concatenate([cols, np.arange(m, m + r)]))
+    y_rows, y_cols = rnd(by_rows[:, :m]), rnd(by_cols[:, :len(cols)])
+    assert relf(y[rows], y_rows) < TOL
+    assert relf(y[:, cols], y_cols) < TOL
+    assert np.max(np.abs(y[rows] - y_rows)) <= 2.0 ** -6 * np.max(np.abs(y_rows))
+    assert np.max(np.abs(y[:, cols] - y_cols)) <= 2.0 ** -6 * np.max(np.abs(y_cols))
+    o_a_ref = oracle.round_bf16(by_cols[:, len(cols):])
+    amax_ref = np.max(np.abs(o_a_ref))
+    assert relf(np_of(layer.o_a), o_a_ref) < TOL
+    assert abs(layer.amax_oa.item() - amax_ref) <= 2.0 ** -7 * amax_ref
+    assert layer.amax_oa.item() == np.max(np.abs(np_of(layer.o_a)))        # consistent with its own output
+    return layer
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_forward(shape, out_dtype):
+    T, n, m, r, k, outliers = shape
+    d, wcat, s_w = _inputs(T, n, m, r, outliers, seed=100 + T)
+    print(f"fwd T={T} n={n} m={m} r={r} {out_dtype}", flush=True)
+    _check_forward(T, n, m, r, k, d, wcat, s_w, out_dtype)
+
+
+def test_forward_exact_integer_case_is_bit_exact():
+    """Small-integer code values, power-of-two scales: every product and partial sum is exact in
+    fp32, so the fp32 output must equal the oracle bit for bit (catches any wrong operand index)."""
+    g = np.random.default_rng(1)
+    T, n, m, r = 300, 256, 272, 16
+    xi = g.integers(-4, 5, size=(T, n)).astype(np.float32)
+    xi[0, 0] = 7.0                                   # amax = 7 -> s_x = 64 exactly
+    wi = g.integers(-8, 9, size=(m + r, n)).astype(np.float32)
+    wcat = oracle.fp8_encode(wi, oracle.E4M3)
+    layer = layer_on_gpu(T, n, m, r, 4, wcat, np.float32(2.0), torch.float32)
+    layer.forward(torch.from_numpy(xi).to(torch.bfloat16).cuda())
+    torch.cuda.synchronize()
+    assert layer.s_x.item() == 64.0
+    ref = oracle.layer_fwd(xi, wcat, np.float32(2.0), m, r)
+    want = (xi.astype(np.float64) @ wi.astype(np.float64).T) / 2.0
+    assert np.array_equal(ref["merged"], want)
+    assert np.array_equal(np_of(layer.y).astype(np.float64), want[:, :m])
+    assert np.array_equal(np_of(layer.o_a).astype(np.float64), oracle.round_bf16(want[:, m:]).astype(np.float64))
+
+
+def _check_backward(T, n, m, r, k, d, wcat, s_w, out_dtype, n_sample=96):
+    x = d["x"].float().numpy()
+    # O_A and its maximum come from the oracle's forward (all rows, adapter columns only)
+    xq, s_x, _ = oracle.quantize(x, oracle.E4M3)
+    o_a = oracle.round_bf16(oracle.melded_fwd(xq, wcat, s_w, s_x, m, r, cols=np.arange(m, m + r)))
+    amax_oa = np.float32(np.max(np.abs(o_a)))
+    g = np.random.default_rng(T)
+    buf0 = (g.normal(size=(m, r)) * 1e-3).astype(np.float32)
+    lr = 2e-4
+    layer = layer_on_gpu(T, n, m, r, k, wcat, s_w, out_dtype)
+    layer.o_a.copy_(torch.from_numpy(o_a).to(torch.bfloat16))
+    layer.amax_oa.fill_(float(amax_oa))
+    layer.delta_buf.copy_(torch.from_numpy(buf0))
+    layer.backward(d["dy"].cuda(), lr=lr)
+    torch.cuda.synchronize()
+    dyq_ref, s_dy_ref, _ = oracle.quantize(d["dy"].float().numpy(), oracle.E5M2)
+    assert np.array_equal(np_of(layer.dyq), dyq_ref)
+    assert np.float32(layer.s_dy.item()).tobytes() == s_dy_ref.tobytes()
+    rnd = (lambda v: v) if out_dtype == torch.float32 else oracle.round_bf16
+    rows = sample_indices(T, n_sample, seed=T + 1)
+    cols = sample_indices(n, n_sample, seed=n + 1)
+    dx = np_of(layer.dx)
+    dx_rows = rnd(oracle.dx(dyq_ref, wcat, s_dy_ref, s_w, m, rows=rows))
+    dx_cols = rnd(oracle.dx(dyq_ref, wcat, s_dy_ref, s_w, m, cols=cols))
+    assert relf(dx[rows], dx_rows) < TOL
+    assert relf(dx[:, cols], dx_cols) < TOL
+    assert np.max(np.abs(dx[rows] - dx_rows)) <= 2.0 ** -6 * np.max(np.abs(dx_rows))
+    assert np.max(np.abs(dx[:, cols] - dx_cols)) <= 2.0 ** -6 * np.max(np.abs(dx_cols))
+    db_ref, _, _ = oracle.db(dyq_ref, s_dy_ref, o_a, amax_oa)
+    assert relf(np_of(layer.d_b), db_ref) < TOL
+    buf_ref = oracle.delta_accumulate(buf0, db_ref, lr)
+    assert relf(np_of(layer.delta_buf) - buf0, buf_ref - buf0) < TOL
+    return layer
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_backward(shape, out_dtype):
+    T, n, m, r, k, outliers = shape
+    d, wcat, s_w = _inputs(T, n, m, r, outliers, seed=200 + T)
+    print(f"bwd T={T} n={n} m={m} r={r} {out_dtype}", flush=True)
+    layer = _check_backward(T, n, m, r, k, d, wcat, s_w, out_dtype)
+    # without a buffer: d_b only
+    layer2 = layer_on_gpu(T, n, m, r, k, wcat, s_w, out_dtype)
+    layer2.o_a.copy_(layer.o_a)
+    layer2.amax_oa.copy_(layer.amax_oa)
+    layer2.backward(d["dy"].cuda(), lr=2e-4, accumulate=False)
+    torch.cuda.synchronize()
+    assert torch.equal(layer2.d_b, layer.d_b)
+    assert torch.count_nonzero(layer2.delta_buf) == 0
+
+
+def test_backward_exact_integer_case_is_bit_exact():
+    g = np.random.default_rng(2)
+    T, n, m, r = 260, 272, 256, 16
+    gi = g.integers(-3, 4, size=(T, m)).astype(np.float32)
+    gi[0, 0] = 7.0                                   # s_dy = 57344 / 7 = 8192 exactly
+    wi = g.integers(-8, 9, size=(m + r, n)).astype(np.float32)
+    oa = g.integers(-3, 4, size=(T, r)).astype(np.float32)
+    oa[0, 0] = 7.0                                   # s_oa = 64
+    wcat = oracle.fp8_encode(wi, oracle.E4M3)
+    layer = layer_on_gpu(T, n, m, r, 4, wcat, np.float32(4.0), torch.float32)
+    layer.o_a.copy_(torch.from_numpy(oa).to(torch.bfloat16))
+    layer.amax_oa.fill_(7.0)
+    layer.backward(torch.from_numpy(gi).to(torch.bfloat16).cuda(), accumulate=False)
+    torch.cuda.synchronize()
+    assert layer.s_dy.item() == 8192.0
+    assert np.array_equal(np_of(layer.dx).astype(np.float64), (gi.astype(np.float64) @ wi[:m].astype(np.float64)) / 4.0)
+    assert np.array_equal(np_of(layer.d_b).astype(np.float64), gi.astype(np.float64).T @ oa.astype(np.float64))
+
+
+UPDATE_CASES = [
+    # n, m, r, k, ties, scale
+    (512, 512, 16, 8, False, 2e-4),
+    (384, 208, 16, 5, True, 0.05),
+    (128, 16, 16, 16, False, 1.0),      # k = m
+    (1024, 1040, 64, 1, True, 0.01),    # k = 1
+    (4096, 4096, 64, 32, True, 2e-3),
+    (272, 528, 32, 50, False, 30.0),    # large steps: saturation
+]
+
+
+@pytest.mark.parametrize("case", UPDATE_CASES)
+@pytest.mark.parametrize("clear", [True, False])
+def test_proxy_update(case, clear):
+    n, m, r, k, ties, scale = case
+    print(f"update n={n} m={m} r={r} k={k} clear={clear}", flush=True)
+    d = workloads.make_inputs(4, n, m, r, seed=300 + m, outliers=False)
+    wcat, s_w = oracle_weights(d["w"], d["a"])
+    buf = workloads.make_delta_buffer(m, r, seed=400 + m, scale=scale, ties=ties).numpy()
+    layer = layer_on_gpu(4, n, m, r, k, wcat, s_w)
+    layer.delta_buf.copy_(torch.from_numpy(buf))
+    layer.update(clear_selected=clear)
+    torch.cuda.synchronize()
+    idx_ref, w_ref, buf_ref = oracle.proxy_update(buf, wcat, m, r, k, clear)
+    assert np.array_equal(np_of(layer.idx), idx_ref)
+    assert np.array_equal(np_of(layer.wq), w_ref)
+    assert np_of(layer.delta_buf).tobytes() == buf_ref.tobytes()
+    if scale >= 0.01:
+        assert np.any(w_ref[:m] != wcat[:m])            # the case really moves some codes
+
+
+def test_proxy_update_all_zero_buffer_selects_first_rows():
+    n, m, r, k = 256, 64, 16, 7
+    d = workloads.make_inputs(4, n, m, r, seed=9)
+    wcat, s_w = oracle_weights(d["w"], d["a"])
+    wcat[0, :3] = [0x80, 0x00, 0x81]
+    layer = layer_on_gpu(4, n, m, r, k, wcat, s_w)
+    layer.update()
+    torch.cuda.synchronize()
+    idx_ref, w_ref, _ = oracle.proxy_update(np.zeros((m, r), np.float32), wcat, m, r, k)
+    assert list(np_of(layer.idx)) == list(range(k)) == list(idx_ref)
+    assert np.array_equal(np_of(layer.wq), w_ref)
+    assert np_of(layer.wq)[0, 0] == 0x00                 # -0 + 0 = +0
+
+
+def test_chained_layer_step_and_determinism():
+    """fwd -> bwd -> update chained on the GPU (each call fed by the previous GPU call) stays
+    within tolerance of the chained oracle, and a second run reproduces every byte."""
+    c = workloads.CONFIGS[1]
+    d = workloads.config_layer_inputs(1)
+    m, n, r, k, T = d["shape"].m, d["shape"].n, c.r, c.k, c.T
+    wcat, s_w = oracle_weights(d["w"], d["a"])
+    outs = []
+    for rep in range(2):
+        layer = fq.MeldedLinear(T, n, m, r, k, out_dtype=torch.bfloat16)
+        layer.init_weights(d["w"].cuda(), d["a"].cuda())
+        layer.forward(d["x"].cuda())
+        layer.backward(d["dy"].cuda(), lr=c.lr)
+        buf_before = layer.delta_buf.clone()
+        layer.update()
+        torch.cuda.synchronize()
+        outs.append([np_of(t).copy() for t in (layer.wq, layer.s_w, layer.y, layer.o_a, layer.amax_oa, layer.dx,
+                                               layer.d_b, layer.delta_buf, layer.idx, buf_before)])
+    for a, b in zip(*outs):
+        assert a.tobytes() == b.tobytes()
+    wq_new, s_w_gpu, y, o_a, amax_oa, dx, d_b, buf_after, idx, buf_before = outs[0]
+    assert np.float32(s_w_gpu[0]).tobytes() == s_w.tobytes()
+    f = oracle.layer_fwd(d["x"].float().numpy(), wcat, s_w, m, r)
+    b = oracle.layer_bwd(d["dy"].float().numpy(), wcat, s_w, f["o_a"], f["amax_oa"], m, r,
+                         delta_buf=np.zeros((m, r), np.float32), lr=c.lr)
+    assert relf(y, oracle.round_bf16(f["y"])) < TOL
+    assert relf(dx, oracle.round_bf16(b["dx"])) < TOL
+    assert relf(d_b, b["db"]) < 2 * TOL                 # O_A differs by bf16 rounding flips at most
+    assert relf(buf_before, b["delta_buf"]) < 2 * TOL
+    # the update applied to the GPU's own buffer must match the oracle applied to those bytes
+    idx_ref, w_ref, buf_ref = oracle.proxy_update(buf_before, wcat, m, r, k)
+    assert np.array_equal(idx, idx_ref) and np.array_equal(wq_new, w_ref)
+    assert buf_after.tobytes() == buf_ref.tobytes()
+
+
+def test_init_weights_matches_oracle_quantizer():
+    d = workloads.make_inputs(8, 1024, 528, 32, seed=17)
+    layer = fq.MeldedLinear(8, 1024, 528, 32, 4)
+    layer.init_weights(d["w"].cuda(), d["a"].cuda())
+    torch.cuda.synchronize()
+    wcat, s_w = oracle_weights(d["w"], d["a"])
+    assert np.array_equal(np_of(layer.wq), wcat)
+    assert np.float32(layer.s_w.item()).tobytes() == s_w.tobytes()
+    assert np.any((wcat[528:] & 0x7F) == 0x7E)           # some adapter entries clip at the backbone's scale
+
+
+@pytest.mark.parametrize("cfg", [2])
+def test_full_size_config_sampled(cfg):
+    """The headline configuration at full size, in the launch configuration the benchmark
+    times: codes and scales in full, GEMM outputs on sampled rows and columns."""
+    c = workloads.CONFIGS[cfg]
+    d = workloads.config_layer_inputs(cfg)
+    m, n = d["shape"].m, d["shape"].n
+    wcat, s_w = oracle_weights(d["w"], d["a"])
+    print(f"config {cfg} forward", flush=True)
+    _check_forward(c.T, n, m, c.r, c.k, d, wcat, s_w, torch.bfloat16, n_sample=64)
+    print(f"config {cfg} backward", flush=True)
+    _check_backward(c.T, n, m, c.r, c.k, d, wcat, s_w, torch.bfloat16, n_sample=64)

@@ -1,0 +1,116 @@
+"""Host-side checks of libfalqon.so that need no GPU: the library loads, exports every symbol
+that include/falqon.h declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2510_24061_amd as fq
+    if not os.path.exists(fq.lib_path()):
+        from paper_2510_24061_amd import build
+        build.build()
+    return fq.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    header = open(os.path.join(ROOT, "include", "falqon.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(falqon_[a-z_]+)\s*\(", header))
+    assert {"falqon_quantize", "falqon_melded_fwd", "falqon_melded_bwd", "falqon_proxy_update",
+            "falqon_workspace_bytes", "falqon_status_string"} <= names
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    import paper_2510_24061_amd as fq
+    assert fq.status_string(0) == "ok"
+    assert len({fq.status_string(i) for i in range(7)}) == 7
+
+
+def test_workspace_bytes(L):
+    import paper_2510_24061_amd as fq
+    assert fq.workspace_bytes(4096, 4096, 4096, 64) >= 4096 + 8 * 4096
+    assert fq.workspace_bytes(4096, 4096, 4096, 64) < 64 << 20
+    assert fq.workspace_bytes(0, 4096, 4096, 64) == 0
+    assert fq.workspace_bytes(16, 4100, 4096, 64) == 0          # n not a multiple of 16
+    assert fq.workspace_bytes(16, 4096, 4096, 272) == 0         # r > 256
+
+
+def _vp(v):
+    return ctypes.c_void_p(v)
+
+
+def test_argument_validation_happens_before_any_launch(L):
+    """Fake, never-dereferenced device addresses: every call must return an error status
+    without launching (this machine may have no GPU at all)."""
+    ok = 0x10000            # 16-byte aligned fake address
+    odd = 0x10004
+    ws_bytes = L.falqon_workspace_bytes(64, 64, 64, 16)
+    q = L.falqon_quantize
+    assert q(None, 0, 4, 16, 16, 0, None, _vp(ok), 16, _vp(ok), None, _vp(ok), 4096, None) == 1      # NULL x
+    assert q(_vp(ok), 7, 4, 16, 16, 0, None, _vp(ok), 16, _vp(ok), None, _vp(ok), 4096, None) == 4   # dtype
+    assert q(_vp(ok), 0, 4, 16, 16, 2, None, _vp(ok), 16, _vp(ok), None, _vp(ok), 4096, None) == 4   # fmt
+    assert q(_vp(ok), 0, 4, 24, 24, 0, None, _vp(ok), 24, _vp(ok), None, _vp(ok), 4096, None) == 2   # cols % 16
+    assert q(_vp(ok), 0, 4, 32, 16, 0, None, _vp(ok), 32, _vp(ok), None, _vp(ok), 4096, None) == 2   # ld < cols
+    assert q(_vp(odd), 0, 4, 16, 16, 0, None, _vp(ok), 16, _vp(ok), None, _vp(ok), 4096, None) == 3  # align
+    assert q(_vp(ok), 0, 4, 16, 16, 0, None, _vp(ok), 16, _vp(ok), None, None, 0, None) == 5         # no ws
+    assert q(_vp(ok), 0, 4, 16, 16, 0, None, _vp(ok), 16, _vp(ok), None, _vp(ok), 100, None) == 5    # small ws
+
+    f = L.falqon_melded_fwd
+    args = dict(x=ok, wq=ok, s_w=ok, T=64, n=64, m=64, r=16, xq=ok, s_x=ok, y=ok, yt=0, o_a=ok, amax=ok,
+                ws=ok, wsb=ws_bytes)
+
+    def fwd(**kw):
+        a = dict(args, **kw)
+        return f(_vp(a["x"]), _vp(a["wq"]), _vp(a["s_w"]), a["T"], a["n"], a["m"], a["r"], _vp(a["xq"]),
+                 _vp(a["s_x"]), _vp(a["y"]), a["yt"], _vp(a["o_a"]), _vp(a["amax"]), _vp(a["ws"]), a["wsb"], None)
+
+    assert fwd(x=None) == 1 and fwd(wq=None) == 1 and fwd(amax=None) == 1
+    assert fwd(T=0) == 2 and fwd(n=72) == 2 and fwd(m=0) == 2 and fwd(r=8) == 2 and fwd(r=512) == 2
+    assert fwd(y=odd) == 3 and fwd(yt=5) == 4
+    assert fwd(ws=None) == 5 and fwd(wsb=ws_bytes - 1) == 5
+
+    b = L.falqon_melded_bwd
+
+    def bwd(**kw):
+        a = dict(dy=ok, wq=ok, s_w=ok, o_a=ok, amax=ok, T=64, n=64, m=64, r=16, dyq=ok, s_dy=ok, dx=ok, dxt=0,
+                 d_b=ok, buf=ok, ws=ok, wsb=ws_bytes)
+        a.update(kw)
+        return b(_vp(a["dy"]), _vp(a["wq"]), _vp(a["s_w"]), _vp(a["o_a"]), _vp(a["amax"]), a["T"], a["n"], a["m"],
+                 a["r"], _vp(a["dyq"]), _vp(a["s_dy"]), _vp(a["dx"]), a["dxt"], _vp(a["d_b"]), _vp(a["buf"]),
+                 ctypes.c_float(1e-3), _vp(a["ws"]), a["wsb"], None)
+
+    assert bwd(dy=None) == 1 and bwd(d_b=None) == 1 and bwd(o_a=None) == 1
+    assert bwd(m=24) == 2 and bwd(T=-1) == 2
+    assert bwd(dx=odd) == 3 and bwd(buf=odd) == 3 and bwd(dxt=9) == 4
+    assert bwd(wsb=0) == 5
+
+    p = L.falqon_proxy_update
+
+    def upd(**kw):
+        a = dict(buf=ok, wq=ok, n=64, m=64, r=16, k=4, idx=ok, ws=ok, wsb=ws_bytes)
+        a.update(kw)
+        return p(_vp(a["buf"]), _vp(a["wq"]), a["n"], a["m"], a["r"], a["k"], _vp(a["idx"]), 1, _vp(a["ws"]),
+                 a["wsb"], None)
+
+    assert upd(buf=None) == 1 and upd(idx=None) == 1
+    assert upd(k=0) == 2 and upd(k=65) == 2 and upd(m=131072, k=1) == 2
+    assert upd(wq=odd) == 3
+    assert upd(ws=None) == 5 and upd(wsb=16) == 5
+
+
+def test_product_path_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2510_24061_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, fn)).read()
+                assert "import oracle" not in text and "from oracle" not in text, fn
+                assert "falqon_oracle" not in text and "orc_" not in text, fn
