@@ -158,6 +158,23 @@ falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int6
                                   int32_t* idx_out, int clear_selected,
                                   void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Building block: one FP8 product with rescale, C = A . op(B) / (s_a * s_b), fp32 accumulation.
+ * This is the FP8 matmul-and-rescale equation on its own; falqon_melded_fwd and
+ * falqon_melded_bwd run the same kernel.  It is exported so that a benchmark can time the
+ * product in isolation and can assemble a conventional separate-path FP8 LoRA layer (the
+ * comparison the paper draws in its preliminary analysis) from the same kernels.
+ *
+ *   a      in   FP8 [M, K], K contiguous, format a_fmt
+ *   b      in   E4M3; b_is_kn = 0: [N, K] (K contiguous); b_is_kn = 1: [K, N] (N contiguous)
+ *   s_a, s_b  in  device scalars
+ *   c      out  [M, N] of dtype ct
+ * K and N must be multiples of 16.
+ */
+falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t* b, int b_is_kn,
+                              int64_t M, int64_t N, int64_t K, const float* s_a, const float* s_b,
+                              void* c, falqon_dtype ct, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -54,6 +54,8 @@ def lib():
                                         f32p, f32p, c.c_float, vp, c.c_size_t, vp]
         L.falqon_proxy_update.restype = c.c_int
         L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
+        L.falqon_fp8_gemm.restype = c.c_int
+        L.falqon_fp8_gemm.argtypes = [vp, c.c_int, vp, c.c_int, i64, i64, i64, f32p, f32p, vp, c.c_int, vp]
         _lib = L
     return _lib
 
@@ -127,6 +129,16 @@ def proxy_update(delta_buf, wq, m: int, r: int, k: int, idx_out, ws, clear_selec
     st = lib().falqon_proxy_update(_p(delta_buf), _p(wq), n, m, r, k, _p(idx_out), 1 if clear_selected else 0,
                                    _p(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_proxy_update")
+
+
+def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c) -> None:
+    """C = A . op(B) / (s_a s_b): a [M,K] FP8; b E4M3 [N,K] or, with b_is_kn, [K,N]."""
+    _dev(a, b, s_a, s_b, c)
+    M, K = a.shape
+    N = b.shape[1] if b_is_kn else b.shape[0]
+    st = lib().falqon_fp8_gemm(_p(a), a_fmt, _p(b), 1 if b_is_kn else 0, M, N, K, _p(s_a), _p(s_b), _p(c),
+                               _dtype_code(c), _stream())
+    _check(st, "falqon_fp8_gemm")
 
 
 class MeldedLinear:

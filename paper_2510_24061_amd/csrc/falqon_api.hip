@@ -176,4 +176,26 @@ falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int6
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 
+falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t* b, int b_is_kn,
+                              int64_t M, int64_t N, int64_t K, const float* s_a, const float* s_b,
+                              void* c, falqon_dtype ct, void* stream)
+{
+    if (a_fmt != FALQON_E4M3 && a_fmt != FALQON_E5M2) return FALQON_ERR_ENUM;
+    if (ct != FALQON_BF16 && ct != FALQON_F32) return FALQON_ERR_ENUM;
+    if (M < 1 || N < 16 || K < 16 || (N % 16) || (K % 16) || M > (int64_t(1) << 24) || N > (int64_t(1) << 20) ||
+        K > (int64_t(1) << 20))
+        return FALQON_ERR_SHAPE;
+    if (!a || !b || !s_a || !s_b || !c) return FALQON_ERR_NULL;
+    if (misaligned(a) || misaligned(b) || misaligned(c)) return FALQON_ERR_ALIGN;
+    GemmArgs g;
+    g.a = a; g.lda = K; g.a_fmt = a_fmt == FALQON_E5M2 ? 1 : 0;
+    g.b = b; g.ldb = b_is_kn ? N : K; g.b_is_kn = b_is_kn ? 1 : 0;
+    g.M = M; g.N = N; g.K = K;
+    g.sa = s_a; g.sb = s_b;
+    g.c0 = c; g.ldc0 = N; g.c0_is_f32 = (ct == FALQON_F32); g.n_split = N;
+    g.c1 = nullptr; g.ldc1 = 0; g.amax1 = nullptr;
+    hipError_t e = launch_gemm(g, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
 }  // extern "C"

@@ -77,7 +77,8 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     const int ph = (tiles_m - panel * PH) < PH ? (tiles_m - panel * PH) : PH;
     const int tile_n = rem / ph, tile_m = panel * PH + (rem - tile_n * ph);
 
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    // wave-uniform values live in scalar registers
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int wm = wave / WN, wn = wave % WN;
     const int64_t m0 = static_cast<int64_t>(tile_m) * BM, n0 = static_cast<int64_t>(tile_n) * BN;
     const int64_t M = g.M, N = g.N, K = g.K;
@@ -162,11 +163,6 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
-    // 32-wide blocks of this wave that hold any valid output (ragged last tiles skip the rest)
-    const int64_t wrow0 = m0 + wm * MB * 32, wcol0 = n0 + wn * NB * 32;
-    int mb_valid = static_cast<int>((M - wrow0 + 31) / 32), nb_valid = static_cast<int>((N - wcol0 + 31) / 32);
-    mb_valid = mb_valid < 0 ? 0 : (mb_valid > MB ? MB : mb_valid);
-    nb_valid = nb_valid < 0 ? 0 : (nb_valid > NB ? NB : nb_valid);
 
     const int KT = static_cast<int>((K + BK - 1) / BK);
     issue_stage(0, 0);
@@ -190,38 +186,80 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
             for (int mi = 0; mi < MB; ++mi)
 #pragma unroll
                 for (int ni = 0; ni < NB; ++ni)
-                    if (mi < mb_valid && ni < nb_valid)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                            af[mi], bf[ni], acc[mi][ni], A_FMT, 0 /* B: E4M3 */, 0, 0, 0, 0);
+                    // weight operand first: the accumulator then holds, per lane, one token row
+                    // and runs of four consecutive output columns (wide, row-contiguous stores)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                        bf[ni], af[mi], acc[mi][ni], 0 /* E4M3 */, A_FMT, 0, 0, 0, 0);
         }
     }
 
-    // ---- epilogue: rescale, split, convert, store -----------------------------------------------
-    // Accumulator layout of a 32x32 block: lane l, register v -> row 8*(v/4) + 4*(l/32) + v%4, col l%32.
+    // ---- epilogue: rescale, convert, stage through LDS, split, store ----------------------------
+    // Accumulator layout of a 32x32 block (weight operand first): lane l holds token row l % 32;
+    // register v holds column 8*(v/4) + 4*(l/32) + v%4 of the block.  One pass per 32-row block
+    // index mi: every wave parks its 32 x (NB*32) strip in LDS, then the workgroup streams the
+    // WM*32 rows out with 16 bytes per lane, row-contiguous.
     const float inv = 1.0f / ((*g.sa) * (*g.sb));
+    const bool f32 = g.c0_is_f32 != 0;
+    const int es = f32 ? 4 : 2;
+    const int pitch = BN * es + 16;                               // +16 B: rows start on different banks
     float oa_max = 0.0f;
+    __syncthreads();                                              // all operand reads are done
 #pragma unroll
     for (int mi = 0; mi < MB; ++mi) {
+        uint8_t* srow = lds + (wm * 32 + (lane & 31)) * pitch;
 #pragma unroll
         for (int ni = 0; ni < NB; ++ni) {
-            if (mi >= mb_valid || ni >= nb_valid) continue;
-            const int64_t col = wcol0 + ni * 32 + (lane & 31);
-            if (col >= N) continue;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t row = wrow0 + mi * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-                if (row >= M) continue;
-                const float val = acc[mi][ni][v] * inv;
-                if (col < g.n_split) {
-                    if (g.c0_is_f32) static_cast<float*>(g.c0)[row * g.ldc0 + col] = val;
-                    else static_cast<uint16_t*>(g.c0)[row * g.ldc0 + col] = bf16_bits_rne(val);
+            for (int q = 0; q < 4; ++q) {
+                const int c = wn * NB * 32 + ni * 32 + q * 8 + (lane >> 5) * 4;
+                const float v0 = acc[mi][ni][4 * q] * inv, v1 = acc[mi][ni][4 * q + 1] * inv;
+                const float v2 = acc[mi][ni][4 * q + 2] * inv, v3 = acc[mi][ni][4 * q + 3] * inv;
+                if (f32) {
+                    *reinterpret_cast<float4*>(srow + c * 4) = make_float4(v0, v1, v2, v3);
                 } else {
-                    const uint16_t b = bf16_bits_rne(val);
-                    static_cast<uint16_t*>(g.c1)[row * g.ldc1 + (col - g.n_split)] = b;
-                    oa_max = fmaxf(oa_max, fabsf(__uint_as_float(static_cast<uint32_t>(b) << 16)));
+                    uint2 pk;
+                    pk.x = bf16_bits_rne(v0) | (static_cast<uint32_t>(bf16_bits_rne(v1)) << 16);
+                    pk.y = bf16_bits_rne(v2) | (static_cast<uint32_t>(bf16_bits_rne(v3)) << 16);
+                    *reinterpret_cast<uint2*>(srow + c * 2) = pk;
                 }
             }
         }
+        __syncthreads();
+        const int segs_per_row = BN * es / 16;
+        const int cols_per_seg = 16 / es;
+        for (int sidx = threadIdx.x; sidx < WM * 32 * segs_per_row; sidx += 64 * NW) {
+            const int srw = sidx / segs_per_row, seg = sidx - srw * segs_per_row;
+            const int64_t row = m0 + (srw >> 5) * (MB * 32) + mi * 32 + (srw & 31);
+            const int64_t col = n0 + seg * cols_per_seg;
+            if (row < M && col < N) {
+                const uint4 d = *reinterpret_cast<const uint4*>(lds + srw * pitch + seg * 16);
+                if (col < g.n_split) {
+                    *reinterpret_cast<uint4*>(static_cast<uint8_t*>(g.c0) + (row * g.ldc0 + col) * es) = d;
+                } else {
+                    uint16_t* dst = static_cast<uint16_t*>(g.c1) + row * g.ldc1 + (col - g.n_split);
+                    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+                    if (f32) {                                     // four fp32 -> four bf16
+                        uint2 pk;
+                        const uint16_t b0 = bf16_bits_rne(__uint_as_float(w[0])), b1 = bf16_bits_rne(__uint_as_float(w[1]));
+                        const uint16_t b2 = bf16_bits_rne(__uint_as_float(w[2])), b3 = bf16_bits_rne(__uint_as_float(w[3]));
+                        pk.x = b0 | (static_cast<uint32_t>(b1) << 16);
+                        pk.y = b2 | (static_cast<uint32_t>(b3) << 16);
+                        *reinterpret_cast<uint2*>(dst) = pk;
+                        oa_max = fmaxf(oa_max, fmaxf(fmaxf(fabsf(__uint_as_float(static_cast<uint32_t>(b0) << 16)),
+                                                           fabsf(__uint_as_float(static_cast<uint32_t>(b1) << 16))),
+                                                     fmaxf(fabsf(__uint_as_float(static_cast<uint32_t>(b2) << 16)),
+                                                           fabsf(__uint_as_float(static_cast<uint32_t>(b3) << 16)))));
+                    } else {
+                        *reinterpret_cast<uint4*>(dst) = d;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            oa_max = fmaxf(oa_max, fmaxf(fabsf(__uint_as_float(w[e] << 16)),
+                                                         fabsf(__uint_as_float(w[e] & 0xffff0000u))));
+                    }
+                }
+            }
+        }
+        __syncthreads();
     }
     if (g.amax1 && n0 + BN > g.n_split) {
         for (int off = 32; off > 0; off >>= 1) oa_max = fmaxf(oa_max, __shfl_xor(oa_max, off, 64));
