@@ -23,6 +23,8 @@
 //     so ragged shapes need no separate code path.
 //   - Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the id -> tile
 //     map hands each XCD a compact block of tiles so its L2 sees each operand panel once.
+#include <cstdlib>
+
 #include "falqon_internal.h"
 
 namespace falqon {
@@ -37,6 +39,9 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 #define FQ_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
 __device__ __attribute__((aligned(16))) uint8_t g_zero16[16];
+#ifdef FQ_EXP_TIMING
+__device__ long long g_dbg[64];
+#endif
 
 constexpr int BK = 128;   // bytes of K per step (two 64-deep MFMAs)
 
@@ -48,6 +53,26 @@ __device__ __forceinline__ int swz_kc(int row) { return ((row >> 1) ^ ((row & 1)
 // Swizzle of a [K][N] tile with CH chunks of 16 B per K-row.
 template <int CH>
 __device__ __forceinline__ int swz_kn(int krow) { return CH >= 16 ? ((krow & 7) << 1) : (krow & (CH - 1)); }
+
+__device__ __forceinline__ const uint8_t* opaque_uniform(const uint8_t* p)
+{
+    const uint64_t u = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u));
+    const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(u >> 32));
+    return reinterpret_cast<const uint8_t*>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+
+// Workgroup barrier that orders LDS accesses only.  __syncthreads() also waits for every
+// outstanding global access, which would drain the global_load_lds fetches that are meant to
+// stay in flight across the barrier; their completion is awaited explicitly where needed.
+__device__ __forceinline__ void barrier_lds_only()
+{
+    asm volatile("" ::: "memory");               // compiler-level: no LDS access moves across
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+}
 
 __device__ __forceinline__ uint16_t bf16_bits_rne(float v)
 {
@@ -61,9 +86,11 @@ __global__ void __launch_bounds__(64 * WM * WN)
 gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk)
 {
     constexpr int BM = WM * MB * 32, BN = WN * NB * 32, NW = WM * WN;
-    constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK, STAGE = A_BYTES + B_BYTES;
+    constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
     static_assert((BM / 8) % NW == 0 && (B_BYTES / 1024) % NW == 0, "loads must split evenly over waves");
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[2 * STAGE];
+    // Operand rings: the left operand three stages deep, the right operand two (160 KB at 256x256).
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[3 * A_BYTES + 2 * B_BYTES];
+    uint8_t* const lds_b = lds + 3 * A_BYTES;
 
     // ---- workgroup -> tile (XCD aware) ----------------------------------------------------
     // Hardware places workgroup b on XCD b % 8.  XCD x takes tiles [x*chunk, (x+1)*chunk) of a
@@ -84,41 +111,92 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     const int64_t M = g.M, N = g.N, K = g.K;
 
     // ---- global -> LDS ----------------------------------------------------------------------
-    auto issue_stage = [&](int kt, int buf) {
-        uint8_t* sA = lds + buf * STAGE;
-        uint8_t* sB = sA + A_BYTES;
-        const int64_t k0 = static_cast<int64_t>(kt) * BK;
+    // Fast path (every K-step that lies fully inside K): address = uniform base + 32-bit lane
+    // offset.  The lane offsets never change; only the scalar base advances with K.  Rows and
+    // columns beyond the matrix are clamped to the last valid one: they load real bytes whose
+    // products land in output elements that are never stored.  The K tail cannot be clamped
+    // (it would add foreign terms to valid outputs); its step fetches out-of-range chunks from
+    // a block of zeros instead (slow path, at most one step per tile).
+    constexpr int IT_A = BM / 8 / NW, IT_B = B_BYTES / 1024 / NW;
+    constexpr int CH = BN / 16;                               // [K][N] tile: chunks per K-row
+    constexpr int RPI = 64 / CH;                              // [K][N] tile: K-rows per wave instruction
+    const int rows_a = static_cast<int>((M - m0) < BM ? (M - m0) : BM);
+    const int rows_b = static_cast<int>((N - n0) < BN ? (N - n0) : BN);   // rows of [N,K] / columns of [K,N]
+    uint32_t off_a[IT_A], off_b[IT_B];
 #pragma unroll
-        for (int it = 0; it < BM / 8 / NW; ++it) {
+    for (int it = 0; it < IT_A; ++it) {
+        const int row = (it * NW + wave) * 8 + (lane >> 3);
+        const int c = (lane & 7) ^ swz_kc(row);
+        const int rr = row < rows_a ? row : rows_a - 1;
+        off_a[it] = static_cast<uint32_t>(rr) * static_cast<uint32_t>(g.lda) + c * 16;
+    }
+#pragma unroll
+    for (int it = 0; it < IT_B; ++it) {
+        if (!B_KN) {
+            const int row = (it * NW + wave) * 8 + (lane >> 3);
+            const int c = (lane & 7) ^ swz_kc(row);
+            const int rr = row < rows_b ? row : rows_b - 1;
+            off_b[it] = static_cast<uint32_t>(rr) * static_cast<uint32_t>(g.ldb) + c * 16;
+        } else {
+            const int krow = (it * NW + wave) * RPI + lane / CH;
+            int c = (lane % CH) ^ swz_kn<CH>(krow);
+            c = c * 16 < rows_b ? c : rows_b / 16 - 1;
+            off_b[it] = static_cast<uint32_t>(krow) * static_cast<uint32_t>(g.ldb) + c * 16;
+        }
+    }
+    const uint8_t* base_a = g.a + m0 * g.lda;
+    const uint8_t* base_b = B_KN ? g.b + n0 : g.b + n0 * g.ldb;
+    const int64_t kstep_b = B_KN ? static_cast<int64_t>(BK) * g.ldb : BK;
+
+    auto dma16 = [&](const uint8_t* src, uint8_t* dst_wave_uniform) {
+        __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(dst_wave_uniform), 16, 0, 0);
+    };
+    // One 1 KB fetch of a stage that lies fully inside K (scalar base, opaque so that the lane
+    // offset stays a separate 32-bit term).
+    auto fetch_a_one = [&](const uint8_t* pa, uint8_t* dst, int j) { dma16(pa + off_a[j], dst + (j * NW + wave) * 1024); };
+    auto fetch_b_one = [&](const uint8_t* pb, uint8_t* dst, int j) { dma16(pb + off_b[j], dst + (j * NW + wave) * 1024); };
+    // All IT_A (IT_B) fetches of one operand tile of stage s, back to back: prologue and K tail.
+    auto fetch_a_all = [&](int s, uint8_t* dst) {
+        const int64_t k0 = static_cast<int64_t>(s) * BK;
+        if (k0 + BK <= K) {
+            const uint8_t* pa = opaque_uniform(base_a + k0);
+#pragma unroll
+            for (int it = 0; it < IT_A; ++it) fetch_a_one(pa, dst, it);
+            return;
+        }
+#pragma unroll
+        for (int it = 0; it < IT_A; ++it) {
             const int i = it * NW + wave;                     // 1 KB = 8 rows per wave instruction
             const int row = i * 8 + (lane >> 3);
             const int c = (lane & 7) ^ swz_kc(row);
             const int64_t gr = m0 + row, gk = k0 + c * 16;
-            const uint8_t* src = (gr < M && gk < K) ? g.a + gr * g.lda + gk : g_zero16;
-            __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(sA + i * 1024), 16, 0, 0);
+            dma16((gr < M && gk < K) ? g.a + gr * g.lda + gk : g_zero16, dst + i * 1024);
         }
-        if (!B_KN) {
+    };
+    auto fetch_b_all = [&](int s, uint8_t* dst) {
+        const int64_t k0 = static_cast<int64_t>(s) * BK;
+        if (k0 + BK <= K) {
+            const uint8_t* pb = opaque_uniform(base_b + s * kstep_b);
 #pragma unroll
-            for (int it = 0; it < BN / 8 / NW; ++it) {
-                const int i = it * NW + wave;
+            for (int it = 0; it < IT_B; ++it) fetch_b_one(pb, dst, it);
+            return;
+        }
+#pragma unroll
+        for (int it = 0; it < IT_B; ++it) {
+            const int i = it * NW + wave;
+            const uint8_t* src;
+            if (!B_KN) {
                 const int row = i * 8 + (lane >> 3);
                 const int c = (lane & 7) ^ swz_kc(row);
                 const int64_t gr = n0 + row, gk = k0 + c * 16;
-                const uint8_t* src = (gr < N && gk < K) ? g.b + gr * g.ldb + gk : g_zero16;
-                __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(sB + i * 1024), 16, 0, 0);
-            }
-        } else {
-            constexpr int CH = BN / 16;                       // chunks per K-row
-            constexpr int RPI = 64 / CH;                      // K-rows per wave instruction
-#pragma unroll
-            for (int it = 0; it < BK / RPI / NW; ++it) {
-                const int i = it * NW + wave;
+                src = (gr < N && gk < K) ? g.b + gr * g.ldb + gk : g_zero16;
+            } else {
                 const int krow = i * RPI + lane / CH;
                 const int c = (lane % CH) ^ swz_kn<CH>(krow);
                 const int64_t gk = k0 + krow, gn = n0 + c * 16;
-                const uint8_t* src = (gk < K && gn < N) ? g.b + gk * g.ldb + gn : g_zero16;
-                __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(sB + i * 1024), 16, 0, 0);
+                src = (gk < K && gn < N) ? g.b + gk * g.ldb + gn : g_zero16;
             }
+            dma16(src, dst + i * 1024);
         }
     };
 
@@ -139,16 +217,21 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     // the address of 8 bytes; lane L receives byte (L % 8) of the eight lanes 2q + (L % 16) / 8.
     // Pointing lane s at K-row (s % 16) / 2, column block 8 * (s % 2) therefore returns to
     // lane L eight consecutive K of column (L % 16): four such reads fill a 32-byte operand.
+    // The read is written as inline assembly: through the builtin the compiler cannot tell that
+    // it does not touch the LDS slots that in-flight global_load_lds fetches are filling, and
+    // makes every such read wait for all of them.  The price is that the compiler no longer
+    // tracks its completion either: every consumer below is preceded by an explicit
+    // s_waitcnt lgkmcnt(0).
     auto read_kn = [&](const uint8_t* tile, int ncol_base, int kh) -> v8i {
-        constexpr int CH = BN / 16;
         v8i r;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int krow = kh * 64 + (lane >> 5) * 32 + t * 8 + ((lane & 15) >> 1);
             const int ncol = ncol_base + ((lane >> 4) & 1) * 16 + (lane & 1) * 8;
             const uint8_t* p = tile + krow * BN + ((((ncol >> 4) ^ swz_kn<CH>(krow)) << 4) | (ncol & 15));
-            const v2i d = __builtin_amdgcn_ds_read_tr8_b64_v2i32(
-                (v2i __attribute__((address_space(3)))*)(p));
+            const uint32_t addr = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(FQ_LDS_PTR(p)));
+            v2i d;
+            asm volatile("ds_read_b64_tr_b8 %0, %1" : "=v"(d) : "v"(addr));
             r[2 * t] = d[0];
             r[2 * t + 1] = d[1];
         }
@@ -165,33 +248,136 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
 
 
     const int KT = static_cast<int>((K + BK - 1) / BK);
-    issue_stage(0, 0);
+#ifdef FQ_EXP_TIMING
+    long long* dbg = g_dbg;
+#define FQ_STAMP(i) if ((i) == 0 && blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0 && kt < 60) dbg[kt] = clock64();
+    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) { dbg[60] = clock64(); dbg[63] = wall_clock64(); }
+#else
+#define FQ_STAMP(i)
+#endif
+    // ---- main loop, software pipelined across K-steps -------------------------------------------
+    // Step k multiplies stage k in two 64-deep halves.  A stage's left tile sits in ring slot
+    // k % 3, its right tile in slot k % 2.
+    //   half 0: MFMAs on operands already in registers.  Under them: read half 1's operands from
+    //           LDS; fetch the LEFT tile of stage k+2 (its slot was last read in step k-1).
+    //   wait until everything but those newest fetches has landed (stage k+1 is complete), barrier:
+    //           now no wave reads the right tile of stage k any more.
+    //   half 1: MFMAs.  Under them: fetch the RIGHT tile of stage k+2 into the slot just freed;
+    //           read half 0's operands of stage k+1.
+    // Fetches are spread one per MFMA: a wave that issues them back to back stalls on the CU's
+    // 64 B/clk vector-memory path while the matrix core drains.  Left-tile fetches have a step and
+    // a half to land, right-tile fetches a full half-step after the last one is issued.  The
+    // barrier is reached with MFMAs still in flight, and no LDS latency is exposed.
+    auto read_a = [&](const uint8_t* sA, int mi, int kh) -> v8i {
+        return read_kc(sA, wm * MB * 32 + mi * 32 + (lane & 31), kh);
+    };
+    auto read_b = [&](const uint8_t* sB, int ni, int kh) -> v8i {
+        if (!B_KN) return read_kc(sB, wn * NB * 32 + ni * 32 + (lane & 31), kh);
+        return read_kn(sB, wn * NB * 32 + ni * 32, kh);
+    };
+    constexpr int N_MFMA = MB * NB, N_FRAG = MB + NB;
+    constexpr int A_PER_SLOT = (IT_A + N_MFMA - 1) / N_MFMA, B_PER_SLOT = (IT_B + N_MFMA - 1) / N_MFMA;
+    constexpr int FRAGS_PER_SLOT = (N_FRAG + N_MFMA - 1) / N_MFMA;
+    // s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] | expcnt << 4 | lgkmcnt << 8 | vmcnt[5:4] << 14)
+    constexpr int WAIT_ALL = 0;
+    constexpr int WAIT_LDS = 0xC07F;                                                            // lgkmcnt 0 only
+    constexpr int WAIT_BUT_A = (IT_A & 15) | (7 << 4) | ((IT_A >> 4) << 14);                    // lgkmcnt 0
+    constexpr int WAIT_BUT_STAGE = ((IT_A + IT_B) & 15) | (7 << 4) | (((IT_A + IT_B) >> 4) << 14);
+
+    v8i af[2][MB], bf[2][NB];
+    // read fragment f (right-operand fragments first) of half kh from a stage
+    auto read_frag = [&](const uint8_t* sA, const uint8_t* sB, int kh, int f) {
+        if (f < NB) bf[kh][f] = read_b(sB, f, kh);
+        else if (f < N_FRAG) af[kh][f - NB] = read_a(sA, f - NB, kh);
+    };
+
+    fetch_a_all(0, lds);
+    fetch_b_all(0, lds_b);
+    if (KT > 1) {
+        fetch_a_all(1, lds + A_BYTES);
+        fetch_b_all(1, lds_b + B_BYTES);
+        __builtin_amdgcn_s_waitcnt(WAIT_BUT_STAGE);           // stage 0 has landed
+    } else {
+        __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+    }
+    barrier_lds_only();
+#pragma unroll
+    for (int f = 0; f < N_FRAG; ++f) read_frag(lds, lds_b, 0, f);
+    __builtin_amdgcn_s_waitcnt(WAIT_LDS);
+
+    int ia = 0;                                               // ring slot of stage kt's left tile
     for (int kt = 0; kt < KT; ++kt) {
-        __builtin_amdgcn_s_waitcnt(0);          // this wave's LDS-DMA loads of step kt have landed
-        __syncthreads();                         // ... everyone's have, and buffer (kt+1)&1 is free
-        if (kt + 1 < KT) issue_stage(kt + 1, (kt + 1) & 1);
-        const uint8_t* sA = lds + (kt & 1) * STAGE;
-        const uint8_t* sB = sA + A_BYTES;
+        FQ_STAMP(0)
+        const int ia1 = ia == 2 ? 0 : ia + 1, ia2 = ia1 == 2 ? 0 : ia1 + 1;
+        const uint8_t* sA = lds + ia * A_BYTES;
+        const uint8_t* sB = lds_b + (kt & 1) * B_BYTES;
+        uint8_t* nA = lds + ia2 * A_BYTES;                     // destination of stage k+2, left
+        uint8_t* nB = lds_b + (kt & 1) * B_BYTES;              // destination of stage k+2, right
+        const bool fetch = kt + 2 < KT;
+        const bool fast = fetch && (static_cast<int64_t>(kt + 3) * BK <= K);
+        const bool next = kt + 1 < KT;
+        const uint8_t* pa = opaque_uniform(base_a + static_cast<int64_t>(kt + 2) * BK);
+        const uint8_t* pb = opaque_uniform(base_b + (kt + 2) * kstep_b);
+        // ---- half 0 ----
+        if (fetch && !fast) fetch_a_all(kt + 2, nA);            // K tail: zero-filled slow path
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
-            v8i af[MB], bf[NB];
-#pragma unroll
-            for (int mi = 0; mi < MB; ++mi) af[mi] = read_kc(sA, wm * MB * 32 + mi * 32 + (lane & 31), kh);
+        for (int mi = 0; mi < MB; ++mi) {
 #pragma unroll
             for (int ni = 0; ni < NB; ++ni) {
-                if (!B_KN) bf[ni] = read_kc(sB, wn * NB * 32 + ni * 32 + (lane & 31), kh);
-                else bf[ni] = read_kn(sB, wn * NB * 32 + ni * 32, kh);
+                const int q = mi * NB + ni;
+                // weight operand first: the accumulator then holds, per lane, one token row
+                // and runs of four consecutive output columns (wide, row-contiguous stores)
+                acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    bf[0][ni], af[0][mi], acc[mi][ni], 0 /* E4M3 */, A_FMT, 0, 0, 0, 0);
+                if (fast) {
+#pragma unroll
+                    for (int u = 0; u < A_PER_SLOT; ++u)
+                        if (q * A_PER_SLOT + u < IT_A) fetch_a_one(pa, nA, q * A_PER_SLOT + u);
+                }
+#pragma unroll
+                for (int u = 0; u < FRAGS_PER_SLOT; ++u) read_frag(sA, sB, 1, q * FRAGS_PER_SLOT + u);
+                __builtin_amdgcn_sched_barrier(0);
             }
-#pragma unroll
-            for (int mi = 0; mi < MB; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < NB; ++ni)
-                    // weight operand first: the accumulator then holds, per lane, one token row
-                    // and runs of four consecutive output columns (wide, row-contiguous stores)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
-                        bf[ni], af[mi], acc[mi][ni], 0 /* E4M3 */, A_FMT, 0, 0, 0, 0);
         }
+        FQ_STAMP(1)
+        // half 1's operands are in registers and stage k+1 has landed (only the left-tile fetches
+        // of stage k+2, issued last, may still be in flight)
+        if (fetch) __builtin_amdgcn_s_waitcnt(WAIT_BUT_A);
+        else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+        FQ_STAMP(2)
+        barrier_lds_only();                                    // ... for every wave
+        FQ_STAMP(3)
+        // ---- half 1 ----
+        const uint8_t* tA = lds + ia1 * A_BYTES;                // stage k+1
+        const uint8_t* tB = lds_b + ((kt + 1) & 1) * B_BYTES;
+        if (fetch && !fast) fetch_b_all(kt + 2, nB);
+#pragma unroll
+        for (int mi = 0; mi < MB; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < NB; ++ni) {
+                const int q = mi * NB + ni;
+                acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
+                    bf[1][ni], af[1][mi], acc[mi][ni], 0 /* E4M3 */, A_FMT, 0, 0, 0, 0);
+                if (fast) {
+#pragma unroll
+                    for (int u = 0; u < B_PER_SLOT; ++u)
+                        if (q * B_PER_SLOT + u < IT_B) fetch_b_one(pb, nB, q * B_PER_SLOT + u);
+                }
+                if (next) {
+#pragma unroll
+                    for (int u = 0; u < FRAGS_PER_SLOT; ++u) read_frag(tA, tB, 0, q * FRAGS_PER_SLOT + u);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(WAIT_LDS);                 // next half 0's operands are in registers
+        FQ_STAMP(4)
+        ia = ia1;
     }
+    __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+#ifdef FQ_EXP_TIMING
+    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[61] = clock64();
+#endif
 
     // ---- epilogue: rescale, convert, stage through LDS, split, store ----------------------------
     // Accumulator layout of a 32x32 block (weight operand first): lane l holds token row l % 32;
@@ -261,6 +447,12 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
         }
         __syncthreads();
     }
+#ifdef FQ_EXP_TIMING
+    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) { dbg[62] = clock64(); dbg[59] = wall_clock64(); }
+    __syncthreads();
+    if (blockIdx.x == FQ_EXP_TIMING && threadIdx.x < 64)
+        reinterpret_cast<long long*>(static_cast<uint8_t*>(g.c0) + (m0 * g.ldc0 + n0) * (g.c0_is_f32 ? 4 : 2))[threadIdx.x] = dbg[threadIdx.x];
+#endif
     if (g.amax1 && n0 + BN > g.n_split) {
         for (int off = 32; off > 0; off >>= 1) oa_max = fmaxf(oa_max, __shfl_xor(oa_max, off, 64));
         // non-negative floats order like their bit patterns
@@ -291,6 +483,18 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream)
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream)
 {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;
+    // Tuning override (development only): FALQON_GEMM_TILE = 0 auto, 1..4 force a tile shape.
+    static const int forced = [] {
+        const char* e = getenv("FALQON_GEMM_TILE");
+        return e ? atoi(e) : 0;
+    }();
+    switch (forced) {
+        case 1: return launch_cfg<2, 2, 4, 4>(g, stream);   // 256x256, 4 waves
+        case 2: return launch_cfg<2, 4, 4, 2>(g, stream);   // 256x256, 8 waves (wave tile 128x64)
+        case 3: return launch_cfg<4, 2, 2, 4>(g, stream);   // 256x256, 8 waves (wave tile 64x128)
+        case 4: return launch_cfg<2, 2, 2, 2>(g, stream);   // 128x128, 4 waves
+        default: break;
+    }
     // Large problems: 256x256 tiles, one workgroup per CU.  Small ones: 128x128 so that more
     // than a handful of CUs take part.
     const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
