@@ -108,25 +108,27 @@ db_partial_kernel(const uint8_t* __restrict__ dyq, const uint16_t* __restrict__ 
             const int trow = threadIdx.x >> 1, half = threadIdx.x & 1;     // 32 ranks per half
             const int64_t gt = t0 + trow;
             uint32_t codes[8];
+            uint4 w[4];
+            // rows and ranks out of range read a block of zeros (address select: a load inside a
+            // branch would be waited for at the join and serialise the four loads)
 #pragma unroll
-            for (int c4 = 0; c4 < 8; ++c4) codes[c4] = 0u;
-            if (gt < t_end) {
+            for (int v8 = 0; v8 < 4; ++v8) {                               // 8 bf16 per 16-byte load
+                const int64_t gp = p0 + half * 32 + v8 * 8;
+                const void* src = (gt < t_end && gp < r) ? static_cast<const void*>(o_a + gt * r + gp)
+                                                         : static_cast<const void*>(g_zero16);
+                w[v8] = *reinterpret_cast<const uint4*>(src);
+            }
 #pragma unroll
-                for (int v8 = 0; v8 < 4; ++v8) {                           // 8 bf16 per 16-byte load
-                    const int64_t gp = p0 + half * 32 + v8 * 8;
-                    if (gp < r) {
-                        const uint4 w = *reinterpret_cast<const uint4*>(o_a + gt * r + gp);
-                        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
-                        float f[8];
+            for (int v8 = 0; v8 < 4; ++v8) {
+                const uint32_t ww[4] = {w[v8].x, w[v8].y, w[v8].z, w[v8].w};
+                float f[8];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            f[2 * e] = __fmul_rn(__uint_as_float(ww[e] << 16), s_oa_scale);
-                            f[2 * e + 1] = __fmul_rn(__uint_as_float(ww[e] & 0xffff0000u), s_oa_scale);
-                        }
-                        codes[2 * v8] = cast4_e4m3(f[0], f[1], f[2], f[3]);
-                        codes[2 * v8 + 1] = cast4_e4m3(f[4], f[5], f[6], f[7]);
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    f[2 * e] = __fmul_rn(__uint_as_float(ww[e] << 16), s_oa_scale);
+                    f[2 * e + 1] = __fmul_rn(__uint_as_float(ww[e] & 0xffff0000u), s_oa_scale);
                 }
+                codes[2 * v8] = cast4_e4m3(f[0], f[1], f[2], f[3]);
+                codes[2 * v8 + 1] = cast4_e4m3(f[4], f[5], f[6], f[7]);
             }
 #pragma unroll
             for (int c = 0; c < 2; ++c) {                                   // two 16-byte chunks
@@ -165,8 +167,9 @@ db_partial_kernel(const uint8_t* __restrict__ dyq, const uint16_t* __restrict__ 
 }
 
 // dB = (sum of partials, split ascending) / (s_dy * s_oa);  delta_buf += -lr * dB
+template <int SPLITS>
 __global__ void __launch_bounds__(kThreads)
-db_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count,
+db_reduce_kernel(const float* __restrict__ partial, int64_t count,
                  const float* __restrict__ s_dy, const float* __restrict__ amax_oa,
                  float* __restrict__ d_b, float* delta_buf, float lr)
 {
@@ -174,10 +177,22 @@ db_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count,
     const float inv = 1.0f / ((*s_dy) * s_oa_scale);
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * 4;
     for (int64_t e = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4; e < count; e += stride) {
-        float4 s = *reinterpret_cast<const float4*>(partial + e);
-        for (int sp = 1; sp < splits; ++sp) {
-            const float4 v = *reinterpret_cast<const float4*>(partial + sp * count + e);
-            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        float4 s;
+        {
+            constexpr int B = SPLITS < 8 ? SPLITS : 8;                // loads in flight per batch
+            float4 v[B];
+#pragma unroll
+            for (int u = 0; u < B; ++u) v[u] = *reinterpret_cast<const float4*>(partial + u * count + e);
+            s = v[0];
+#pragma unroll
+            for (int u = 1; u < B; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+#pragma unroll
+            for (int sp0 = B; sp0 < SPLITS; sp0 += B) {
+#pragma unroll
+                for (int u = 0; u < B; ++u) v[u] = *reinterpret_cast<const float4*>(partial + (sp0 + u) * count + e);
+#pragma unroll
+                for (int u = 0; u < B; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+            }
         }
         s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
         *reinterpret_cast<float4*>(d_b + e) = s;
@@ -201,8 +216,9 @@ int db_splits(int64_t T, int64_t m)
     const int64_t max_by_tokens = (T + BT - 1) / BT;
     if (splits > max_by_tokens) splits = max_by_tokens;
     if (splits > kDbSplitMax) splits = kDbSplitMax;
-    if (splits < 1) splits = 1;
-    return static_cast<int>(splits);
+    int p2 = 1;                                              // round down to a power of two
+    while (p2 * 2 <= splits) p2 *= 2;
+    return p2;
 }
 
 hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, const float* amax_oa,
@@ -220,10 +236,17 @@ hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, con
     if (e != hipSuccess) return e;
     const int64_t count = m * r;
     int64_t blocks = (count / 4 + kThreads - 1) / kThreads;
-    if (blocks > 1024) blocks = 1024;
     if (blocks < 1) blocks = 1;
-    db_reduce_kernel<<<static_cast<unsigned>(blocks), kThreads, 0, stream>>>(partials, splits, count, s_dy, amax_oa,
-                                                                             d_b, delta_buf, lr);
+    const unsigned nb = static_cast<unsigned>(blocks);
+    switch (splits) {
+        case 1: db_reduce_kernel<1><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
+        case 2: db_reduce_kernel<2><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
+        case 4: db_reduce_kernel<4><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
+        case 8: db_reduce_kernel<8><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
+        case 16: db_reduce_kernel<16><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
+        case 32: db_reduce_kernel<32><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
+        default: return hipErrorInvalidValue;                // db_splits() only returns powers of two
+    }
     return hipGetLastError();
 }
 

@@ -13,10 +13,22 @@ WsLayout ws_layout(int64_t T, int64_t n, int64_t m, int64_t r)
     size_t off = 0;
     w.amax_partials = off; off = align_up(off + sizeof(float) * kMaxAmaxBlocks, 256);
     w.scores = off;        off = align_up(off + sizeof(double) * static_cast<size_t>(m), 256);
+    w.delta_sel = off;     off = align_up(off + sizeof(float) * static_cast<size_t>(m) * static_cast<size_t>(r), 256);
     w.db_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(db_splits(T, m)) *
                                                     static_cast<size_t>(m) * static_cast<size_t>(r), 256);
+    w.oa_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(oa_splits(T, r)) *
+                                                    static_cast<size_t>(T) * static_cast<size_t>(r), 256);
     w.total = off;
     return w;
+}
+
+int oa_splits(int64_t T, int64_t r)
+{
+    // the O_A product runs on 128x128 tiles; split K until about one workgroup per CU
+    const int64_t tiles = ((T + 127) / 128) * ((r + 127) / 128);
+    int s = 1;
+    while (s < 8 && tiles * s * 2 <= 256) s *= 2;               // a power of two, at most 8
+    return s;
 }
 
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -103,15 +115,41 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
                                    reinterpret_cast<uint32_t*>(amax_oa), st);
     if (e != hipSuccess) return FALQON_ERR_HIP;
 
-    // O_merged <- x~ W~'^T / (s_w s_x), split into y and O_A
+    // O_merged <- x~ W~'^T / (s_w s_x), split into y and O_A.  When the r adapter columns fit
+    // into the last, partly empty tile column of the backbone product they ride along in the one
+    // GEMM; otherwise they would add a whole, almost empty tile column (a second wave over the
+    // CUs), and are formed by the skinny kernel from the same x~ instead.
+    const int64_t tile = gemm_tile_n(T, m + r);
+    const bool merged = (m + r + tile - 1) / tile == (m + tile - 1) / tile;
     GemmArgs g;
     g.a = xq; g.lda = n; g.a_fmt = 0;
     g.b = wq; g.ldb = n; g.b_is_kn = 0;
-    g.M = T; g.N = m + r; g.K = n;
+    g.M = T; g.N = merged ? m + r : m; g.K = n;
     g.sa = s_x; g.sb = s_w;
     g.c0 = y; g.ldc0 = m; g.c0_is_f32 = (yt == FALQON_F32); g.n_split = m;
     g.c1 = o_a; g.ldc1 = r; g.amax1 = reinterpret_cast<uint32_t*>(amax_oa);
     e = launch_gemm(g, st);
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+    if (!merged) {
+        // O_A <- x~ A~^T / (s_w s_x): same kernel, K split over workgroups, fp32 partials, then one
+        // pass that adds them in order, rounds to bf16 and takes the maximum
+        const int splits = oa_splits(T, r);
+        int64_t kps = (n + splits - 1) / splits;
+        kps = (kps + 127) / 128 * 128;
+        float* part = reinterpret_cast<float*>(w8 + L.oa_partials);
+        GemmArgs h;
+        h.a = xq; h.lda = n; h.a_fmt = 0;
+        h.b = wq + m * n; h.ldb = n; h.b_is_kn = 0;
+        h.M = T; h.N = r; h.K = n;
+        h.sa = s_x; h.sb = s_w;
+        h.c0 = part; h.ldc0 = r; h.c0_is_f32 = 1; h.n_split = r;
+        h.c1 = nullptr; h.ldc1 = 0; h.amax1 = nullptr;
+        h.splits = splits; h.k_per_split = kps;
+        e = launch_gemm(h, st);
+        if (e != hipSuccess) return FALQON_ERR_HIP;
+        e = launch_sum_partials_bf16(part, splits, T * r, static_cast<uint16_t*>(o_a),
+                                     reinterpret_cast<uint32_t*>(amax_oa), st);
+    }
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 
@@ -168,11 +206,12 @@ falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int6
     if (misaligned(delta_buf) || misaligned(wq) || (reinterpret_cast<uintptr_t>(idx_out) & 3u))
         return FALQON_ERR_ALIGN;
     const WsLayout L = ws_layout(1, n, m, r);
-    if (!ws || ws_bytes < L.scores + sizeof(double) * static_cast<size_t>(m)) return FALQON_ERR_WORKSPACE;
+    if (!ws || ws_bytes < L.db_partials) return FALQON_ERR_WORKSPACE;
     if (misaligned(ws)) return FALQON_ERR_ALIGN;
     uint8_t* w8 = static_cast<uint8_t*>(ws);
     hipError_t e = launch_proxy_update(delta_buf, wq, n, m, r, k, idx_out, clear_selected,
-                                       reinterpret_cast<double*>(w8 + L.scores), static_cast<hipStream_t>(stream));
+                                       reinterpret_cast<double*>(w8 + L.scores),
+                                       reinterpret_cast<float*>(w8 + L.delta_sel), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 

@@ -17,7 +17,9 @@ constexpr int kDbSplitMax = 32;        // upper bound on the token splits of the
 struct WsLayout {
     size_t amax_partials;   // float[kMaxAmaxBlocks]
     size_t scores;          // double[m]
+    size_t delta_sel;       // float[m][r]: buffer rows picked by the proxy update, in rank order
     size_t db_partials;     // float[splits][m][r]
+    size_t oa_partials;     // float[splits][T][r]
     size_t total;
 };
 WsLayout ws_layout(int64_t T, int64_t n, int64_t m, int64_t r);
@@ -44,8 +46,16 @@ struct GemmArgs {
     const float* sa; const float* sb;              // device scalars
     void* c0; int64_t ldc0; int c0_is_f32; int64_t n_split;
     void* c1; int64_t ldc1; uint32_t* amax1;
+    int splits = 1; int64_t k_per_split = int64_t(1) << 40;   // split K: c0 becomes [splits][M][ldc0] partials
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
+int64_t gemm_tile_n(int64_t M, int64_t N);   // width of the output tiles launch_gemm picks for an M x N product
+
+// ---- O_A from split-K partials (partials.hip) ---------------------------------------------------
+// out[count] (bf16) = sum over splits of partial[split][count]; folds max|out| into *amax.
+hipError_t launch_sum_partials_bf16(const float* partial, int splits, int64_t count, uint16_t* out, uint32_t* amax,
+                                    hipStream_t stream);
+int oa_splits(int64_t T, int64_t r);
 
 // ---- adapter gradient (db.hip) -------------------------------------------------------------
 hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, const float* amax_oa,
@@ -54,6 +64,7 @@ hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, con
 
 // ---- proxy update (proxy.hip) ----------------------------------------------------------------
 hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
-                               int32_t* idx_out, int clear_selected, double* scores, hipStream_t stream);
+                               int32_t* idx_out, int clear_selected, double* scores, float* delta_sel,
+                               hipStream_t stream);
 
 }  // namespace falqon

@@ -108,7 +108,15 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int wm = wave / WN, wn = wave % WN;
     const int64_t m0 = static_cast<int64_t>(tile_m) * BM, n0 = static_cast<int64_t>(tile_n) * BN;
-    const int64_t M = g.M, N = g.N, K = g.K;
+    const int64_t M = g.M, N = g.N;
+    // Split K: workgroup row blockIdx.y multiplies the K range [kbeg, kbeg + K) only and writes
+    // its own copy of the output (fp32 partials, summed by a later pass).
+    const int64_t kbeg = static_cast<int64_t>(blockIdx.y) * g.k_per_split;
+    const int64_t K = (g.K - kbeg) < g.k_per_split ? (g.K - kbeg > 0 ? g.K - kbeg : 0) : g.k_per_split;
+    const uint8_t* const ga = g.a + kbeg;
+    const uint8_t* const gb = B_KN ? g.b + kbeg * g.ldb : g.b + kbeg;
+    uint8_t* const c0p = static_cast<uint8_t*>(g.c0) +
+                         static_cast<int64_t>(blockIdx.y) * M * g.ldc0 * (g.c0_is_f32 ? 4 : 2);
 
     // ---- global -> LDS ----------------------------------------------------------------------
     // Fast path (every K-step that lies fully inside K): address = uniform base + 32-bit lane
@@ -144,8 +152,8 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
             off_b[it] = static_cast<uint32_t>(krow) * static_cast<uint32_t>(g.ldb) + c * 16;
         }
     }
-    const uint8_t* base_a = g.a + m0 * g.lda;
-    const uint8_t* base_b = B_KN ? g.b + n0 : g.b + n0 * g.ldb;
+    const uint8_t* base_a = ga + m0 * g.lda;
+    const uint8_t* base_b = B_KN ? gb + n0 : gb + n0 * g.ldb;
     const int64_t kstep_b = B_KN ? static_cast<int64_t>(BK) * g.ldb : BK;
 
     auto dma16 = [&](const uint8_t* src, uint8_t* dst_wave_uniform) {
@@ -170,7 +178,7 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
             const int row = i * 8 + (lane >> 3);
             const int c = (lane & 7) ^ swz_kc(row);
             const int64_t gr = m0 + row, gk = k0 + c * 16;
-            dma16((gr < M && gk < K) ? g.a + gr * g.lda + gk : g_zero16, dst + i * 1024);
+            dma16((gr < M && gk < K) ? ga + gr * g.lda + gk : g_zero16, dst + i * 1024);
         }
     };
     auto fetch_b_all = [&](int s, uint8_t* dst) {
@@ -189,12 +197,12 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
                 const int row = i * 8 + (lane >> 3);
                 const int c = (lane & 7) ^ swz_kc(row);
                 const int64_t gr = n0 + row, gk = k0 + c * 16;
-                src = (gr < N && gk < K) ? g.b + gr * g.ldb + gk : g_zero16;
+                src = (gr < N && gk < K) ? gb + gr * g.ldb + gk : g_zero16;
             } else {
                 const int krow = i * RPI + lane / CH;
                 const int c = (lane % CH) ^ swz_kn<CH>(krow);
                 const int64_t gk = k0 + krow, gn = n0 + c * 16;
-                src = (gk < K && gn < N) ? g.b + gk * g.ldb + gn : g_zero16;
+                src = (gk < K && gn < N) ? gb + gk * g.ldb + gn : g_zero16;
             }
             dma16(src, dst + i * 1024);
         }
@@ -389,6 +397,9 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     const int es = f32 ? 4 : 2;
     const int pitch = BN * es + 16;                               // +16 B: rows start on different banks
     float oa_max = 0.0f;
+#ifdef FQ_EXP_TIMING
+    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[50] = clock64() + (inv == 0.123f);
+#endif
     __syncthreads();                                              // all operand reads are done
 #pragma unroll
     for (int mi = 0; mi < MB; ++mi) {
@@ -420,7 +431,13 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
             if (row < M && col < N) {
                 const uint4 d = *reinterpret_cast<const uint4*>(lds + srw * pitch + seg * 16);
                 if (col < g.n_split) {
-                    *reinterpret_cast<uint4*>(static_cast<uint8_t*>(g.c0) + (row * g.ldc0 + col) * es) = d;
+                    // streaming store: every workgroup writes 512-byte row segments of its tile at the
+                    // same time; written through the cache as ordinary stores this pattern reaches
+                    // less than half of the write bandwidth that non-temporal stores reach
+                    typedef unsigned v4u __attribute__((ext_vector_type(4)));
+                    const v4u dd = {d.x, d.y, d.z, d.w};
+                    __builtin_nontemporal_store(
+                        dd, reinterpret_cast<v4u*>(c0p + (row * g.ldc0 + col) * es));
                 } else {
                     uint16_t* dst = static_cast<uint16_t*>(g.c1) + row * g.ldc1 + (col - g.n_split);
                     const uint32_t w[4] = {d.x, d.y, d.z, d.w};
@@ -446,12 +463,15 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
             }
         }
         __syncthreads();
+#ifdef FQ_EXP_TIMING
+        if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[51 + mi] = clock64();
+#endif
     }
 #ifdef FQ_EXP_TIMING
     if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) { dbg[62] = clock64(); dbg[59] = wall_clock64(); }
     __syncthreads();
     if (blockIdx.x == FQ_EXP_TIMING && threadIdx.x < 64)
-        reinterpret_cast<long long*>(static_cast<uint8_t*>(g.c0) + (m0 * g.ldc0 + n0) * (g.c0_is_f32 ? 4 : 2))[threadIdx.x] = dbg[threadIdx.x];
+        reinterpret_cast<long long*>(c0p + (m0 * g.ldc0 + n0) * (g.c0_is_f32 ? 4 : 2))[threadIdx.x] = dbg[threadIdx.x];
 #endif
     if (g.amax1 && n0 + BN > g.n_split) {
         for (int off = 32; off > 0; off >>= 1) oa_max = fmaxf(oa_max, __shfl_xor(oa_max, off, 64));
@@ -467,7 +487,7 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream)
     const int tiles_m = static_cast<int>((g.M + BM - 1) / BM), tiles_n = static_cast<int>((g.N + BN - 1) / BN);
     const int total = tiles_m * tiles_n;
     const int chunk = (total + 7) / 8;
-    const dim3 grid(static_cast<unsigned>(chunk * 8)), block(64 * WM * WN);
+    const dim3 grid(static_cast<unsigned>(chunk * 8), static_cast<unsigned>(g.splits)), block(64 * WM * WN);
     if (g.b_is_kn) {
         if (g.a_fmt == 0) gemm_fp8_kernel<WM, WN, MB, NB, true, 0><<<grid, block, 0, stream>>>(g, tiles_m, tiles_n, chunk);
         else gemm_fp8_kernel<WM, WN, MB, NB, true, 1><<<grid, block, 0, stream>>>(g, tiles_m, tiles_n, chunk);
@@ -480,25 +500,29 @@ hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream)
 
 }  // namespace
 
+static bool use_big_tiles(int64_t M, int64_t N)
+{
+    // Large problems: 256x256 tiles, one workgroup per CU.  Small ones: 128x128 so that more
+    // than a handful of CUs take part.
+    return ((M + 255) / 256) * ((N + 255) / 256) >= 128;
+}
+
+int64_t gemm_tile_n(int64_t M, int64_t N) { return use_big_tiles(M, N) ? 256 : 128; }
+
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream)
 {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;
-    // Tuning override (development only): FALQON_GEMM_TILE = 0 auto, 1..4 force a tile shape.
+    // Tuning override (development only): FALQON_GEMM_TILE = 1 forces 256x256 tiles, 4 forces 128x128.
     static const int forced = [] {
         const char* e = getenv("FALQON_GEMM_TILE");
         return e ? atoi(e) : 0;
     }();
     switch (forced) {
         case 1: return launch_cfg<2, 2, 4, 4>(g, stream);   // 256x256, 4 waves
-        case 2: return launch_cfg<2, 4, 4, 2>(g, stream);   // 256x256, 8 waves (wave tile 128x64)
-        case 3: return launch_cfg<4, 2, 2, 4>(g, stream);   // 256x256, 8 waves (wave tile 64x128)
         case 4: return launch_cfg<2, 2, 2, 2>(g, stream);   // 128x128, 4 waves
         default: break;
     }
-    // Large problems: 256x256 tiles, one workgroup per CU.  Small ones: 128x128 so that more
-    // than a handful of CUs take part.
-    const int64_t big_tiles = ((g.M + 255) / 256) * ((g.N + 255) / 256);
-    if (big_tiles >= 128) return launch_cfg<2, 2, 4, 4>(g, stream);
+    if (use_big_tiles(g.M, g.N)) return launch_cfg<2, 2, 4, 4>(g, stream);
     return launch_cfg<2, 2, 2, 2>(g, stream);
 }
 

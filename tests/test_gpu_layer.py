@@ -25,6 +25,8 @@ SHAPES = [
     (300, 1024, 1040, 64, 32, True),      # m + r = 1104: four and a bit 256-wide tiles
     (520, 272, 528, 32, 16, True),        # K tails: n = 272 and m = 528 are not multiples of 128
     (2100, 1024, 4112, 48, 12, True),     # enough tiles for the 256x256 path, ragged tails
+    (130, 256, 256, 160, 8, False),       # wide adapter: five 32-column blocks in the skinny product
+    (64, 128, 512, 256, 4, False),        # largest rank
 ]
 
 
