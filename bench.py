@@ -25,6 +25,9 @@ import workloads  # noqa: E402
 METRIC = "melded FP8 LoRA layer fwd+bwd tokens/sec and % FP8 MFMA peak, 7B shapes"
 FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+# HBM bytes per launch of the forward GEMM kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# runs of this command (see profiles/); None until measured.
+GEMM_FWD_TRAFFIC_BYTES = None
 
 
 def _time_region(fn, iters):
@@ -86,6 +89,51 @@ def bf16_lora_layer(T, n, m, r, iters):
     return _time_region(step, iters)
 
 
+def separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, iters):
+    """Context only: a conventional FP8 LoRA layer with a separate adapter path, assembled from
+    this library's own unfused kernels (quantizer, FP8 GEMM).  Per step it quantizes X, A, B, O_A,
+    dY and dY.B and runs the backbone product plus four small-rank products; the two
+    token-contracted adapter gradients use library bf16 GEMMs (which favours this path)."""
+    dev = "cuda"
+    u8, f32, bf16 = torch.uint8, torch.float32, torch.bfloat16
+    ws = torch.empty(fq.workspace_bytes(T, n, m, r), dtype=u8, device=dev)
+    wq = torch.empty(m, n, dtype=u8, device=dev); s_w = torch.zeros(1, device=dev)
+    fq.quantize(w, fq.E4M3, wq, s_w, ws)
+    b = (torch.randn(m, r, device=dev) * 0.01).to(bf16)
+    xq = torch.empty(T, n, dtype=u8, device=dev); s_x = torch.zeros(1, device=dev)
+    aq = torch.empty(r, n, dtype=u8, device=dev); s_a = torch.zeros(1, device=dev)
+    bq = torch.empty(m, r, dtype=u8, device=dev); s_b = torch.zeros(1, device=dev)
+    oa = torch.empty(T, r, dtype=bf16, device=dev); oaq = torch.empty(T, r, dtype=u8, device=dev); s_oa = torch.zeros(1, device=dev)
+    y0 = torch.empty(T, m, dtype=bf16, device=dev); y1 = torch.empty(T, m, dtype=bf16, device=dev)
+    dyq = torch.empty(T, m, dtype=u8, device=dev); s_dy = torch.zeros(1, device=dev)
+    dx0 = torch.empty(T, n, dtype=bf16, device=dev); dx1 = torch.empty(T, n, dtype=bf16, device=dev)
+    g = torch.empty(T, r, dtype=bf16, device=dev); gq = torch.empty(T, r, dtype=u8, device=dev); s_g = torch.zeros(1, device=dev)
+    a_bf = a.to(bf16)
+
+    def step():
+        fq.quantize(x, fq.E4M3, xq, s_x, ws)
+        fq.quantize(a_bf, fq.E4M3, aq, s_a, ws)
+        fq.quantize(b, fq.E4M3, bq, s_b, ws)
+        fq.fp8_gemm(xq, fq.E4M3, wq, False, s_x, s_w, y0)
+        fq.fp8_gemm(xq, fq.E4M3, aq, False, s_x, s_a, oa)
+        fq.quantize(oa, fq.E4M3, oaq, s_oa, ws)
+        fq.fp8_gemm(oaq, fq.E4M3, bq, False, s_oa, s_b, y1)
+        y = y0 + y1
+        fq.quantize(dy, fq.E5M2, dyq, s_dy, ws)
+        fq.fp8_gemm(dyq, fq.E5M2, wq, True, s_dy, s_w, dx0)
+        fq.fp8_gemm(dyq, fq.E5M2, bq, True, s_dy, s_b, g)
+        fq.quantize(g, fq.E5M2, gq, s_g, ws)
+        fq.fp8_gemm(gq, fq.E5M2, aq, True, s_g, s_a, dx1)
+        dx = dx0 + dx1
+        db = dy.t() @ oa
+        da = g.t() @ x
+        return y, dx, db, da
+
+    for _ in range(3):
+        step()
+    return _time_region(step, iters)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -93,6 +141,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload (2 = the headline LLaMA-7B attention projection)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-context", action="store_true",
+                    help="skip the bf16 LoRA and separate-path FP8 LoRA comparison layers (profiling runs: their "
+                         "launches of the same GEMM kernel at other sizes would blur its per-kernel statistics)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=256)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -131,23 +182,31 @@ def main():
     ms_fwd = _time_region(lambda: layer.forward(x), it)
     ms_bwd = _time_region(lambda: layer.backward(dy, lr=cfg.lr), it)
     ms_upd = _time_region(lambda: layer.update(), it)
-    y_tmp = torch.empty(T, m + r, dtype=torch.bfloat16, device="cuda")
-    ms_gemm_fwd = _time_region(lambda: fq.fp8_gemm(layer.xq, fq.E4M3, layer.wq, False, layer.s_x, layer.s_w, y_tmp), it)
+    # the forward backbone product as falqon_melded_fwd launches it (the r adapter columns are a
+    # separate split-K launch of the same kernel)
+    y_tmp = torch.empty(T, m, dtype=torch.bfloat16, device="cuda")
+    ms_gemm_fwd = _time_region(lambda: fq.fp8_gemm(layer.xq, fq.E4M3, layer.wq[:m], False, layer.s_x, layer.s_w, y_tmp), it)
     ms_gemm_dx = _time_region(lambda: fq.fp8_gemm(layer.dyq, fq.E5M2, layer.wq[:m], True, layer.s_dy, layer.s_w,
                                                   layer.dx), it)
     s_tmp = torch.zeros(1, device="cuda")
     ms_quant = _time_region(lambda: fq.quantize(x, fq.E4M3, layer.xq, s_tmp, layer.ws), it)
     del y_tmp
 
-    flops_fwd = 2.0 * T * n * (m + r)
+    flops_fwd = 2.0 * T * n * m
+    # one plain device-to-device copy of known size: the reference that scales the FETCH_SIZE /
+    # WRITE_SIZE counters when this command runs under rocprofv3 --pmc
+    calib = torch.empty_like(x)
+    calib.copy_(x)
+    torch.cuda.synchronize()
+    del calib
     flops_dx = 2.0 * T * m * n
     flops_db = 2.0 * T * m * r
     tflops_fwd = flops_fwd / (ms_gemm_fwd * 1e-3) / 1e12
     tflops_dx = flops_dx / (ms_gemm_dx * 1e-3) / 1e12
     quant_bytes = 3.0 * T * n                      # read bf16 once (second read is cache-served), write FP8
-    roofline = {"bound": "mfma", "kernel": "gemm_fp8_kernel (forward, X~ . [W~;A~]^T)",
+    roofline = {"bound": "mfma", "kernel": "gemm_fp8_kernel<2,2,4,4,false,0> (forward, X~ . W~^T, 256 tiles of 256x256)",
                 "achieved": tflops_fwd, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": tflops_fwd / FP8_PEAK_TFLOPS, "traffic": None,
+                "frac": tflops_fwd / FP8_PEAK_TFLOPS, "traffic": GEMM_FWD_TRAFFIC_BYTES,
                 "flops_per_launch": flops_fwd, "avg_launch_ms": ms_gemm_fwd}
     kernels = {
         "gemm_fwd": {"ms": ms_gemm_fwd, "TFLOP/s": tflops_fwd, "frac_fp8_peak": tflops_fwd / FP8_PEAK_TFLOPS},
@@ -155,12 +214,19 @@ def main():
         "quantize_x": {"ms": ms_quant, "GB/s": quant_bytes / (ms_quant * 1e-3) / 1e9,
                        "frac_hbm_peak": quant_bytes / (ms_quant * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "calls": {"melded_fwd_ms": ms_fwd, "melded_bwd_ms": ms_bwd, "proxy_update_ms": ms_upd},
-        "gemm_flops_share": {"fwd": flops_fwd, "dx": flops_dx, "db": flops_db},
+        "gemm_flops": {"fwd_backbone": flops_fwd, "fwd_adapter": 2.0 * T * n * r, "dx": flops_dx, "db": flops_db},
     }
 
-    ms_bf16 = bf16_lora_layer(T, n, m, r, max(5, args.steps // 2))
-    context = {"bf16_lora_layer_ms": ms_bf16, "melded_vs_bf16_lora": ms_bf16 / ms_per_step,
+    ms_fwd_bwd = ms_fwd + ms_bwd
+    context = {"melded_fwd_bwd_ms": ms_fwd_bwd, "melded_fwd_bwd_update_ms": ms_per_step,
                "paper": "about 3x over prior quantized-LoRA methods, 1.22x over separate-path FP8, on one RTX 4090"}
+    if not args.no_context:
+        ms_bf16 = bf16_lora_layer(T, n, m, r, max(5, args.steps // 2))
+        ms_sep = separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, d["w"].cuda(), d["a"].cuda(),
+                                              max(5, args.steps // 2))
+        context.update({"bf16_lora_layer_ms": ms_bf16, "separate_path_fp8_lora_layer_ms": ms_sep,
+                        "speedup_vs_separate_path_fp8": ms_sep / ms_fwd_bwd,
+                        "speedup_vs_bf16_lora": ms_bf16 / ms_fwd_bwd})
 
     out = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,

@@ -24,6 +24,7 @@
 //   - Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the id -> tile
 //     map hands each XCD a compact block of tiles so its L2 sees each operand panel once.
 #include <cstdlib>
+#include <type_traits>
 
 #include "falqon_internal.h"
 
@@ -74,11 +75,13 @@ __device__ __forceinline__ void barrier_lds_only()
     asm volatile("" ::: "memory");
 }
 
-__device__ __forceinline__ uint16_t bf16_bits_rne(float v)
+// two fp32 -> two bf16 (round to nearest even) in one dword: v_cvt_pk_bf16_f32
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(v);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return static_cast<uint16_t>(u >> 16);
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    const v2f f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));
 }
 
 template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT>
@@ -314,20 +317,24 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     __builtin_amdgcn_s_waitcnt(WAIT_LDS);
 
     int ia = 0;                                               // ring slot of stage kt's left tile
-    for (int kt = 0; kt < KT; ++kt) {
+    // One K-step.  STEADY = true is the body for steps whose stage k+2 exists and lies fully inside
+    // K: every "is there a next stage" test is resolved at compile time, so the steady-state loop
+    // carries no branches between its MFMAs.
+    auto k_step = [&](int kt, auto steady_tag) {
+        constexpr bool STEADY = decltype(steady_tag)::value;
         FQ_STAMP(0)
         const int ia1 = ia == 2 ? 0 : ia + 1, ia2 = ia1 == 2 ? 0 : ia1 + 1;
         const uint8_t* sA = lds + ia * A_BYTES;
         const uint8_t* sB = lds_b + (kt & 1) * B_BYTES;
         uint8_t* nA = lds + ia2 * A_BYTES;                     // destination of stage k+2, left
         uint8_t* nB = lds_b + (kt & 1) * B_BYTES;              // destination of stage k+2, right
-        const bool fetch = kt + 2 < KT;
-        const bool fast = fetch && (static_cast<int64_t>(kt + 3) * BK <= K);
-        const bool next = kt + 1 < KT;
+        const bool fetch = STEADY || kt + 2 < KT;
+        const bool fast = STEADY || (fetch && (static_cast<int64_t>(kt + 3) * BK <= K));
+        const bool next = STEADY || kt + 1 < KT;
         const uint8_t* pa = opaque_uniform(base_a + static_cast<int64_t>(kt + 2) * BK);
         const uint8_t* pb = opaque_uniform(base_b + (kt + 2) * kstep_b);
         // ---- half 0 ----
-        if (fetch && !fast) fetch_a_all(kt + 2, nA);            // K tail: zero-filled slow path
+        if (!STEADY && fetch && !fast) fetch_a_all(kt + 2, nA); // K tail: zero-filled slow path
 #pragma unroll
         for (int mi = 0; mi < MB; ++mi) {
 #pragma unroll
@@ -337,7 +344,7 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
                 // and runs of four consecutive output columns (wide, row-contiguous stores)
                 acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                     bf[0][ni], af[0][mi], acc[mi][ni], 0 /* E4M3 */, A_FMT, 0, 0, 0, 0);
-                if (fast) {
+                if (STEADY || fast) {
 #pragma unroll
                     for (int u = 0; u < A_PER_SLOT; ++u)
                         if (q * A_PER_SLOT + u < IT_A) fetch_a_one(pa, nA, q * A_PER_SLOT + u);
@@ -350,7 +357,7 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
         FQ_STAMP(1)
         // half 1's operands are in registers and stage k+1 has landed (only the left-tile fetches
         // of stage k+2, issued last, may still be in flight)
-        if (fetch) __builtin_amdgcn_s_waitcnt(WAIT_BUT_A);
+        if (STEADY || fetch) __builtin_amdgcn_s_waitcnt(WAIT_BUT_A);
         else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
         FQ_STAMP(2)
         barrier_lds_only();                                    // ... for every wave
@@ -358,7 +365,7 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
         // ---- half 1 ----
         const uint8_t* tA = lds + ia1 * A_BYTES;                // stage k+1
         const uint8_t* tB = lds_b + ((kt + 1) & 1) * B_BYTES;
-        if (fetch && !fast) fetch_b_all(kt + 2, nB);
+        if (!STEADY && fetch && !fast) fetch_b_all(kt + 2, nB);
 #pragma unroll
         for (int mi = 0; mi < MB; ++mi) {
 #pragma unroll
@@ -366,12 +373,12 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
                 const int q = mi * NB + ni;
                 acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                     bf[1][ni], af[1][mi], acc[mi][ni], 0 /* E4M3 */, A_FMT, 0, 0, 0, 0);
-                if (fast) {
+                if (STEADY || fast) {
 #pragma unroll
                     for (int u = 0; u < B_PER_SLOT; ++u)
                         if (q * B_PER_SLOT + u < IT_B) fetch_b_one(pb, nB, q * B_PER_SLOT + u);
                 }
-                if (next) {
+                if (STEADY || next) {
 #pragma unroll
                     for (int u = 0; u < FRAGS_PER_SLOT; ++u) read_frag(tA, tB, 0, q * FRAGS_PER_SLOT + u);
                 }
@@ -381,7 +388,11 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
         __builtin_amdgcn_s_waitcnt(WAIT_LDS);                 // next half 0's operands are in registers
         FQ_STAMP(4)
         ia = ia1;
-    }
+    };
+    const int steady_steps = static_cast<int>(K / BK) - 2;     // steps whose stage k+2 is a full stage
+    int kt = 0;
+    for (; kt < steady_steps; ++kt) k_step(kt, std::true_type{});
+    for (; kt < KT; ++kt) k_step(kt, std::false_type{});
     __builtin_amdgcn_s_waitcnt(WAIT_ALL);
 #ifdef FQ_EXP_TIMING
     if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[61] = clock64();
@@ -393,80 +404,79 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     // index mi: every wave parks its 32 x (NB*32) strip in LDS, then the workgroup streams the
     // WM*32 rows out with 16 bytes per lane, row-contiguous.
     const float inv = 1.0f / ((*g.sa) * (*g.sb));
-    const bool f32 = g.c0_is_f32 != 0;
-    const int es = f32 ? 4 : 2;
-    const int pitch = BN * es + 16;                               // +16 B: rows start on different banks
     float oa_max = 0.0f;
-#ifdef FQ_EXP_TIMING
-    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[50] = clock64() + (inv == 0.123f);
-#endif
     __syncthreads();                                              // all operand reads are done
+    // the output type is a run-time argument; each of the two bodies is compiled with it fixed
+    auto epilogue = [&](auto is_f32) {
+        constexpr bool F32 = decltype(is_f32)::value;
+        constexpr int ES = F32 ? 4 : 2;
+        constexpr int PITCH = BN * ES + 16;                       // +16 B: rows start on different banks
+        constexpr int SEGS = BN * ES / 16, COLS_PER_SEG = 16 / ES;
 #pragma unroll
-    for (int mi = 0; mi < MB; ++mi) {
-        uint8_t* srow = lds + (wm * 32 + (lane & 31)) * pitch;
+        for (int mi = 0; mi < MB; ++mi) {
+            uint8_t* srow = lds + (wm * 32 + (lane & 31)) * PITCH;
 #pragma unroll
-        for (int ni = 0; ni < NB; ++ni) {
+            for (int ni = 0; ni < NB; ++ni) {
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int c = wn * NB * 32 + ni * 32 + q * 8 + (lane >> 5) * 4;
-                const float v0 = acc[mi][ni][4 * q] * inv, v1 = acc[mi][ni][4 * q + 1] * inv;
-                const float v2 = acc[mi][ni][4 * q + 2] * inv, v3 = acc[mi][ni][4 * q + 3] * inv;
-                if (f32) {
-                    *reinterpret_cast<float4*>(srow + c * 4) = make_float4(v0, v1, v2, v3);
-                } else {
-                    uint2 pk;
-                    pk.x = bf16_bits_rne(v0) | (static_cast<uint32_t>(bf16_bits_rne(v1)) << 16);
-                    pk.y = bf16_bits_rne(v2) | (static_cast<uint32_t>(bf16_bits_rne(v3)) << 16);
-                    *reinterpret_cast<uint2*>(srow + c * 2) = pk;
-                }
-            }
-        }
-        __syncthreads();
-        const int segs_per_row = BN * es / 16;
-        const int cols_per_seg = 16 / es;
-        for (int sidx = threadIdx.x; sidx < WM * 32 * segs_per_row; sidx += 64 * NW) {
-            const int srw = sidx / segs_per_row, seg = sidx - srw * segs_per_row;
-            const int64_t row = m0 + (srw >> 5) * (MB * 32) + mi * 32 + (srw & 31);
-            const int64_t col = n0 + seg * cols_per_seg;
-            if (row < M && col < N) {
-                const uint4 d = *reinterpret_cast<const uint4*>(lds + srw * pitch + seg * 16);
-                if (col < g.n_split) {
-                    // streaming store: every workgroup writes 512-byte row segments of its tile at the
-                    // same time; written through the cache as ordinary stores this pattern reaches
-                    // less than half of the write bandwidth that non-temporal stores reach
-                    typedef unsigned v4u __attribute__((ext_vector_type(4)));
-                    const v4u dd = {d.x, d.y, d.z, d.w};
-                    __builtin_nontemporal_store(
-                        dd, reinterpret_cast<v4u*>(c0p + (row * g.ldc0 + col) * es));
-                } else {
-                    uint16_t* dst = static_cast<uint16_t*>(g.c1) + row * g.ldc1 + (col - g.n_split);
-                    const uint32_t w[4] = {d.x, d.y, d.z, d.w};
-                    if (f32) {                                     // four fp32 -> four bf16
-                        uint2 pk;
-                        const uint16_t b0 = bf16_bits_rne(__uint_as_float(w[0])), b1 = bf16_bits_rne(__uint_as_float(w[1]));
-                        const uint16_t b2 = bf16_bits_rne(__uint_as_float(w[2])), b3 = bf16_bits_rne(__uint_as_float(w[3]));
-                        pk.x = b0 | (static_cast<uint32_t>(b1) << 16);
-                        pk.y = b2 | (static_cast<uint32_t>(b3) << 16);
-                        *reinterpret_cast<uint2*>(dst) = pk;
-                        oa_max = fmaxf(oa_max, fmaxf(fmaxf(fabsf(__uint_as_float(static_cast<uint32_t>(b0) << 16)),
-                                                           fabsf(__uint_as_float(static_cast<uint32_t>(b1) << 16))),
-                                                     fmaxf(fabsf(__uint_as_float(static_cast<uint32_t>(b2) << 16)),
-                                                           fabsf(__uint_as_float(static_cast<uint32_t>(b3) << 16)))));
+                for (int q = 0; q < 4; ++q) {
+                    const int c = wn * NB * 32 + ni * 32 + q * 8 + (lane >> 5) * 4;
+                    const float v0 = acc[mi][ni][4 * q] * inv, v1 = acc[mi][ni][4 * q + 1] * inv;
+                    const float v2 = acc[mi][ni][4 * q + 2] * inv, v3 = acc[mi][ni][4 * q + 3] * inv;
+                    if (F32) {
+                        *reinterpret_cast<float4*>(srow + c * 4) = make_float4(v0, v1, v2, v3);
                     } else {
-                        *reinterpret_cast<uint4*>(dst) = d;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            oa_max = fmaxf(oa_max, fmaxf(fabsf(__uint_as_float(w[e] << 16)),
-                                                         fabsf(__uint_as_float(w[e] & 0xffff0000u))));
+                        uint2 pk;
+                        pk.x = pack_bf16x2(v0, v1);
+                        pk.y = pack_bf16x2(v2, v3);
+                        *reinterpret_cast<uint2*>(srow + c * 2) = pk;
                     }
                 }
             }
-        }
-        __syncthreads();
+            __syncthreads();
+#pragma unroll
+            for (int it = 0; it < WM * 32 * SEGS / (64 * NW); ++it) {
+                const int sidx = it * 64 * NW + threadIdx.x;
+                const int srw = sidx / SEGS, seg = sidx % SEGS;
+                const int64_t row = m0 + (srw >> 5) * (MB * 32) + mi * 32 + (srw & 31);
+                const int64_t col = n0 + seg * COLS_PER_SEG;
+                if (row < M && col < N) {
+                    const uint4 d = *reinterpret_cast<const uint4*>(lds + srw * PITCH + seg * 16);
+                    if (col < g.n_split) {
+                        // streaming store: every workgroup writes 512-byte row segments of its tile at
+                        // the same time; the output is not read again by this layer
+                        typedef unsigned v4u __attribute__((ext_vector_type(4)));
+                        const v4u dd = {d.x, d.y, d.z, d.w};
+                        __builtin_nontemporal_store(dd, reinterpret_cast<v4u*>(c0p + (row * g.ldc0 + col) * ES));
+                    } else {
+                        uint16_t* dst = static_cast<uint16_t*>(g.c1) + row * g.ldc1 + (col - g.n_split);
+                        const uint32_t w[4] = {d.x, d.y, d.z, d.w};
+                        if (F32) {                                 // four fp32 -> four bf16
+                            uint2 pk;
+                            pk.x = pack_bf16x2(__uint_as_float(w[0]), __uint_as_float(w[1]));
+                            pk.y = pack_bf16x2(__uint_as_float(w[2]), __uint_as_float(w[3]));
+                            *reinterpret_cast<uint2*>(dst) = pk;
+                            oa_max = fmaxf(oa_max, fmaxf(fmaxf(fabsf(__uint_as_float(pk.x << 16)),
+                                                               fabsf(__uint_as_float(pk.x & 0xffff0000u))),
+                                                         fmaxf(fabsf(__uint_as_float(pk.y << 16)),
+                                                               fabsf(__uint_as_float(pk.y & 0xffff0000u)))));
+                        } else {
+                            *reinterpret_cast<uint4*>(dst) = d;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                oa_max = fmaxf(oa_max, fmaxf(fabsf(__uint_as_float(w[e] << 16)),
+                                                             fabsf(__uint_as_float(w[e] & 0xffff0000u))));
+                        }
+                    }
+                }
+            }
+            __syncthreads();
 #ifdef FQ_EXP_TIMING
-        if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[51 + mi] = clock64();
+            if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[51 + mi] = clock64();
 #endif
-    }
+        }
+    };
+    if (g.c0_is_f32) epilogue(std::true_type{});
+    else epilogue(std::false_type{});
 #ifdef FQ_EXP_TIMING
     if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) { dbg[62] = clock64(); dbg[59] = wall_clock64(); }
     __syncthreads();
