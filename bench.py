@@ -26,8 +26,8 @@ METRIC = "melded FP8 LoRA layer fwd+bwd tokens/sec and % FP8 MFMA peak, 7B shape
 FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the forward GEMM kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# runs of this command (see profiles/); None until measured.
-GEMM_FWD_TRAFFIC_BYTES = None
+# runs of this command (profiles/bench_config2_pmc_hbm_traffic_and_mfma.md).
+GEMM_FWD_TRAFFIC_BYTES = 137.2e6   # 101.8 MB fetched (FETCH_SIZE x 1.998) + 35.4 MB written
 
 
 def _time_region(fn, iters):
