@@ -44,9 +44,9 @@ def _time_region(fn, iters):
     return start.elapsed_time(stop) / iters
 
 
-def cpu_baseline(cfg, d, sample_tokens):
+def cpu_baseline(cfg, d, sample_tokens, reps):
     """The CPU oracle, as it stands, on the first `sample_tokens` tokens of the same workload
-    taken as one batch: quantize, merged forward, backward and proxy update."""
+    taken as one batch: quantize, merged forward, backward and proxy update, `reps` times."""
     import oracle
     m, n, r, k = d["shape"].m, d["shape"].n, cfg.r, cfg.k
     x = d["x"][:sample_tokens].float().numpy()
@@ -55,14 +55,15 @@ def cpu_baseline(cfg, d, sample_tokens):
     aq, _, _ = oracle.quantize(d["a"].numpy(), oracle.E4M3, scale_in=s_w)
     wcat = np.concatenate([wq, aq])
     t0 = time.perf_counter()
-    f = oracle.layer_fwd(x, wcat, s_w, m, r)
-    b = oracle.layer_bwd(dy, wcat, s_w, f["o_a"], f["amax_oa"], m, r,
-                         delta_buf=np.zeros((m, r), np.float32), lr=cfg.lr)
-    oracle.proxy_update(b["delta_buf"], wcat, m, r, k)
+    for _ in range(reps):
+        f = oracle.layer_fwd(x, wcat, s_w, m, r)
+        b = oracle.layer_bwd(dy, wcat, s_w, f["o_a"], f["amax_oa"], m, r,
+                             delta_buf=np.zeros((m, r), np.float32), lr=cfg.lr)
+        oracle.proxy_update(b["delta_buf"], wcat, m, r, k)
     dt = time.perf_counter() - t0
-    return {"value": sample_tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+    return {"value": reps * sample_tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
             "sample": f"first {sample_tokens} of {cfg.T} tokens of the same workload as one batch, "
-                      f"fwd+bwd+update once ({dt:.1f} s)"}
+                      f"fwd+bwd+update {reps} times ({dt:.1f} s)"}
 
 
 def bf16_lora_layer(T, n, m, r, iters):
@@ -144,7 +145,8 @@ def main():
     ap.add_argument("--no-context", action="store_true",
                     help="skip the bf16 LoRA and separate-path FP8 LoRA comparison layers (profiling runs: their "
                          "launches of the same GEMM kernel at other sizes would blur its per-kernel statistics)")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=256)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
+    ap.add_argument("--cpu-reps", type=int, default=4)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -238,7 +240,7 @@ def main():
         "roofline": roofline, "kernels": kernels, "context": context,
     }
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, d, args.cpu_sample_tokens)
+        out["cpu_baseline"] = cpu_baseline(cfg, d, min(args.cpu_sample_tokens, T), args.cpu_reps)
     print(json.dumps(out))
 
 

@@ -12,15 +12,16 @@
 //   - v_mfma_f32_32x32x64_f8f6f4 (the 8-bit path that runs at the full FP8 rate; the older
 //     32x32x16 FP8 instruction runs at half of it), fp32 accumulators in registers.
 //   - A workgroup owns a BM x BN output tile and walks K in steps of 128 bytes.  Operand
-//     tiles go HBM/L2 -> LDS with global_load_lds (16 B per lane, no register staging),
-//     double buffered: the loads of step k+1 are in flight while step k is multiplied.
+//     tiles go HBM/L2 -> LDS with global_load_lds (16 B per lane, no register staging) into
+//     rings three (left operand) and two (right operand) stages deep: the fetches of step k+2
+//     are issued while step k is multiplied.
 //   - global_load_lds writes lanes to consecutive LDS addresses, so the bank-conflict
 //     swizzle is applied on the global side: lane -> (row, physical chunk) is fixed, and
 //     the lane fetches the logical chunk that belongs there.
 //   - The [K,N] operand is read from LDS with ds_read_b64_tr_b8, which hands each lane
 //     eight consecutive K for one N: exactly the matrix-core operand layout.
-//   - Out-of-range rows, columns and the K tail are fetched from a 16-byte block of zeros,
-//     so ragged shapes need no separate code path.
+//   - Out-of-range rows and columns are clamped to the last valid one (their products land in
+//     outputs that are never stored); the K tail is fetched from a 16-byte block of zeros.
 //   - Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the id -> tile
 //     map hands each XCD a compact block of tiles so its L2 sees each operand panel once.
 #include <cstdlib>
@@ -40,9 +41,6 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 #define FQ_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
 __device__ __attribute__((aligned(16))) uint8_t g_zero16[16];
-#ifdef FQ_EXP_TIMING
-__device__ long long g_dbg[64];
-#endif
 
 constexpr int BK = 128;   // bytes of K per step (two 64-deep MFMAs)
 
@@ -257,15 +255,7 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.0f;
 
-
     const int KT = static_cast<int>((K + BK - 1) / BK);
-#ifdef FQ_EXP_TIMING
-    long long* dbg = g_dbg;
-#define FQ_STAMP(i) if ((i) == 0 && blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0 && kt < 60) dbg[kt] = clock64();
-    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) { dbg[60] = clock64(); dbg[63] = wall_clock64(); }
-#else
-#define FQ_STAMP(i)
-#endif
     // ---- main loop, software pipelined across K-steps -------------------------------------------
     // Step k multiplies stage k in two 64-deep halves.  A stage's left tile sits in ring slot
     // k % 3, its right tile in slot k % 2.
@@ -322,7 +312,6 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     // carries no branches between its MFMAs.
     auto k_step = [&](int kt, auto steady_tag) {
         constexpr bool STEADY = decltype(steady_tag)::value;
-        FQ_STAMP(0)
         const int ia1 = ia == 2 ? 0 : ia + 1, ia2 = ia1 == 2 ? 0 : ia1 + 1;
         const uint8_t* sA = lds + ia * A_BYTES;
         const uint8_t* sB = lds_b + (kt & 1) * B_BYTES;
@@ -354,14 +343,11 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        FQ_STAMP(1)
         // half 1's operands are in registers and stage k+1 has landed (only the left-tile fetches
         // of stage k+2, issued last, may still be in flight)
         if (STEADY || fetch) __builtin_amdgcn_s_waitcnt(WAIT_BUT_A);
         else __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-        FQ_STAMP(2)
         barrier_lds_only();                                    // ... for every wave
-        FQ_STAMP(3)
         // ---- half 1 ----
         const uint8_t* tA = lds + ia1 * A_BYTES;                // stage k+1
         const uint8_t* tB = lds_b + ((kt + 1) & 1) * B_BYTES;
@@ -386,7 +372,6 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
             }
         }
         __builtin_amdgcn_s_waitcnt(WAIT_LDS);                 // next half 0's operands are in registers
-        FQ_STAMP(4)
         ia = ia1;
     };
     const int steady_steps = static_cast<int>(K / BK) - 2;     // steps whose stage k+2 is a full stage
@@ -394,9 +379,6 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     for (; kt < steady_steps; ++kt) k_step(kt, std::true_type{});
     for (; kt < KT; ++kt) k_step(kt, std::false_type{});
     __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-#ifdef FQ_EXP_TIMING
-    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[61] = clock64();
-#endif
 
     // ---- epilogue: rescale, convert, stage through LDS, split, store ----------------------------
     // Accumulator layout of a 32x32 block (weight operand first): lane l holds token row l % 32;
@@ -470,19 +452,10 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
                 }
             }
             __syncthreads();
-#ifdef FQ_EXP_TIMING
-            if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) dbg[51 + mi] = clock64();
-#endif
         }
     };
     if (g.c0_is_f32) epilogue(std::true_type{});
     else epilogue(std::false_type{});
-#ifdef FQ_EXP_TIMING
-    if (blockIdx.x == FQ_EXP_TIMING && wave == 3 && lane == 0) { dbg[62] = clock64(); dbg[59] = wall_clock64(); }
-    __syncthreads();
-    if (blockIdx.x == FQ_EXP_TIMING && threadIdx.x < 64)
-        reinterpret_cast<long long*>(c0p + (m0 * g.ldc0 + n0) * (g.c0_is_f32 ? 4 : 2))[threadIdx.x] = dbg[threadIdx.x];
-#endif
     if (g.amax1 && n0 + BN > g.n_split) {
         for (int off = 32; off > 0; off >>= 1) oa_max = fmaxf(oa_max, __shfl_xor(oa_max, off, 64));
         // non-negative floats order like their bit patterns
