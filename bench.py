@@ -90,6 +90,23 @@ def bf16_lora_layer(T, n, m, r, iters):
     return _time_region(step, iters)
 
 
+def library_fp8_gemm(T, n, m, iters):
+    """Context only: the vendor library's FP8 GEMM (torch._scaled_mm, per-tensor scales, bf16 output)
+    at the shape of the forward backbone product, on random E4M3 operands."""
+    dev = "cuda"
+    g = torch.Generator(device=dev).manual_seed(2)
+    a = torch.randn(T, n, device=dev, generator=g).to(torch.float8_e4m3fn)
+    b = torch.randn(m, n, device=dev, generator=g).to(torch.float8_e4m3fn)
+    one = torch.ones((), device=dev)
+
+    def run():
+        return torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16)
+
+    for _ in range(3):
+        run()
+    return _time_region(run, iters)
+
+
 def separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, iters):
     """Context only: a conventional FP8 LoRA layer with a separate adapter path, assembled from
     this library's own unfused kernels (quantizer, FP8 GEMM).  Per step it quantizes X, A, B, O_A,
@@ -206,6 +223,7 @@ def main():
     tflops_fwd = flops_fwd / (ms_gemm_fwd * 1e-3) / 1e12
     tflops_dx = flops_dx / (ms_gemm_dx * 1e-3) / 1e12
     quant_bytes = 3.0 * T * n                      # read bf16 once (second read is cache-served), write FP8
+    upd_bytes = 4.0 * m * r + 2.0 * k * n + r * n + 8.0 * k * r   # scores + selected rows in/out + adapter rows + buffer rows
     roofline = {"bound": "mfma", "kernel": "gemm_fp8_kernel<2,2,4,4,false,0> (forward, X~ . W~^T, 256 tiles of 256x256)",
                 "achieved": tflops_fwd, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": tflops_fwd / FP8_PEAK_TFLOPS, "traffic": GEMM_FWD_TRAFFIC_BYTES,
@@ -215,6 +233,9 @@ def main():
         "gemm_dx": {"ms": ms_gemm_dx, "TFLOP/s": tflops_dx, "frac_fp8_peak": tflops_dx / FP8_PEAK_TFLOPS},
         "quantize_x": {"ms": ms_quant, "GB/s": quant_bytes / (ms_quant * 1e-3) / 1e9,
                        "frac_hbm_peak": quant_bytes / (ms_quant * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "proxy_update": {"ms": ms_upd, "GB/s": upd_bytes / (ms_upd * 1e-3) / 1e9,
+                         "frac_hbm_peak": upd_bytes / (ms_upd * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "note": "three dependent launches over 1.6 MB: latency bound"},
         "calls": {"melded_fwd_ms": ms_fwd, "melded_bwd_ms": ms_bwd, "proxy_update_ms": ms_upd},
         "gemm_flops": {"fwd_backbone": flops_fwd, "fwd_adapter": 2.0 * T * n * r, "dx": flops_dx, "db": flops_db},
     }
@@ -226,6 +247,11 @@ def main():
         ms_bf16 = bf16_lora_layer(T, n, m, r, max(5, args.steps // 2))
         ms_sep = separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, d["w"].cuda(), d["a"].cuda(),
                                               max(5, args.steps // 2))
+        try:
+            context["library_fp8_gemm_ms"] = library_fp8_gemm(T, n, m, max(5, args.steps // 2))
+        except Exception as exc:  # the library path is context only; its absence must not fail the benchmark
+            context["library_fp8_gemm_ms"] = None
+            context["library_fp8_gemm_error"] = repr(exc)[:200]
         context.update({"bf16_lora_layer_ms": ms_bf16, "separate_path_fp8_lora_layer_ms": ms_sep,
                         "speedup_vs_separate_path_fp8": ms_sep / ms_fwd_bwd,
                         "speedup_vs_bf16_lora": ms_bf16 / ms_fwd_bwd})

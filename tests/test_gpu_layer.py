@@ -27,6 +27,11 @@ SHAPES = [
     (2100, 1024, 4112, 48, 12, True),     # enough tiles for the 256x256 path, ragged tails
     (130, 256, 256, 160, 8, False),       # wide adapter: five 32-column blocks in the skinny product
     (64, 128, 512, 256, 4, False),        # largest rank
+    # adapter columns formed in the quantizer's cast pass (they would start a tile column of their own)
+    (100, 336, 384, 48, 8, True),         # ragged rows, K = 2 chunks of 128 and a tail of 80
+    (50, 2176, 256, 64, 8, False),        # widest adapter of that path, 17 K chunks over 16 waves
+    (33, 640, 128, 32, 4, False),
+    (40, 384, 128, 96, 4, False),         # wider than that: split-K launch
 ]
 
 
@@ -74,11 +79,14 @@ def test_forward(shape, out_dtype):
     _check_forward(T, n, m, r, k, d, wcat, s_w, out_dtype)
 
 
-def test_forward_exact_integer_case_is_bit_exact():
+@pytest.mark.parametrize("T,n,m,r", [(300, 256, 272, 16),     # adapter columns inside the backbone GEMM
+                                     (300, 400, 256, 48),     # ... formed in the cast pass
+                                     (70, 2304, 128, 64),
+                                     (40, 256, 128, 160)])    # ... by the split-K launch
+def test_forward_exact_integer_case_is_bit_exact(T, n, m, r):
     """Small-integer code values, power-of-two scales: every product and partial sum is exact in
     fp32, so the fp32 output must equal the oracle bit for bit (catches any wrong operand index)."""
     g = np.random.default_rng(1)
-    T, n, m, r = 300, 256, 272, 16
     xi = g.integers(-4, 5, size=(T, n)).astype(np.float32)
     xi[0, 0] = 7.0                                   # amax = 7 -> s_x = 64 exactly
     wi = g.integers(-8, 9, size=(m + r, n)).astype(np.float32)
@@ -256,15 +264,25 @@ def test_init_weights_matches_oracle_quantizer():
     assert np.any((wcat[528:] & 0x7F) == 0x7E)           # some adapter entries clip at the backbone's scale
 
 
-@pytest.mark.parametrize("cfg", [2])
-def test_full_size_config_sampled(cfg):
-    """The headline configuration at full size, in the launch configuration the benchmark
+@pytest.mark.parametrize("cfg,layer", [(2, 0), (3, 0), (3, 1), (4, 0), (4, 1), (4, 2)])
+def test_full_size_config_sampled(cfg, layer):
+    """The LLaMA-shaped configurations at full size, in the launch configuration the benchmark
     times: codes and scales in full, GEMM outputs on sampled rows and columns."""
     c = workloads.CONFIGS[cfg]
-    d = workloads.config_layer_inputs(cfg)
+    d = workloads.config_layer_inputs(cfg, layer)
     m, n = d["shape"].m, d["shape"].n
     wcat, s_w = oracle_weights(d["w"], d["a"])
-    print(f"config {cfg} forward", flush=True)
-    _check_forward(c.T, n, m, c.r, c.k, d, wcat, s_w, torch.bfloat16, n_sample=64)
-    print(f"config {cfg} backward", flush=True)
-    _check_backward(c.T, n, m, c.r, c.k, d, wcat, s_w, torch.bfloat16, n_sample=64)
+    print(f"config {cfg} layer {layer} ({m}x{n}, T={c.T}) forward", flush=True)
+    _check_forward(c.T, n, m, c.r, c.k, d, wcat, s_w, torch.bfloat16, n_sample=48)
+    print(f"config {cfg} layer {layer} backward", flush=True)
+    _check_backward(c.T, n, m, c.r, c.k, d, wcat, s_w, torch.bfloat16, n_sample=48)
+    print(f"config {cfg} layer {layer} update", flush=True)
+    buf = workloads.make_delta_buffer(m, c.r, seed=cfg * 10 + layer, ties=True)
+    layer_gpu = layer_on_gpu(c.T, n, m, c.r, c.k, wcat, s_w, torch.bfloat16)
+    layer_gpu.delta_buf.copy_(buf)
+    layer_gpu.update()
+    torch.cuda.synchronize()
+    idx_ref, w_ref, buf_ref = oracle.proxy_update(buf.numpy(), wcat, m, c.r, c.k)
+    assert np.array_equal(np_of(layer_gpu.idx), idx_ref)
+    assert np.array_equal(np_of(layer_gpu.wq), w_ref)
+    assert np_of(layer_gpu.delta_buf).tobytes() == buf_ref.tobytes()
