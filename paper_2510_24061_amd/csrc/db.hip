@@ -68,14 +68,20 @@ __device__ __forceinline__ uint32_t cast4_e4m3(float a, float b, float c, float 
 }
 
 // grid: (ceil(m / BI), splits, ceil(r / BP)); partial[split][m][r]
+// The workgroup's token range is walked in groups of kTiles tiles of BT tokens.  All fetches of a
+// group are issued together, so a workgroup pays one memory latency per group, not per tile (the
+// matrix-core work per tile is a few hundred cycles; the kernel is all memory latency otherwise).
+constexpr int kTiles = 4;
+constexpr int kTileBytes = BT * BI + BT * BP;                          // dyq tile + O_A tile (codes)
+constexpr size_t kDbLdsBytes = static_cast<size_t>(kTiles) * kTileBytes;
+
 __global__ void __launch_bounds__(kThreads)
 db_partial_kernel(const uint8_t* __restrict__ dyq, const uint16_t* __restrict__ o_a,
                   const float* __restrict__ amax_oa, int64_t T, int64_t m, int64_t r,
                   int64_t tokens_per_split, float* __restrict__ partial)
 {
     constexpr int CH_DY = BI / 16, CH_OA = BP / 16;
-    __shared__ __attribute__((aligned(1024))) uint8_t s_dy[BT * BI];   // [token][feature i]
-    __shared__ __attribute__((aligned(1024))) uint8_t s_oa[BT * BP];   // [token][rank p]
+    extern __shared__ __attribute__((aligned(1024))) uint8_t s_tiles[];   // [tile]{[token][feature i], [token][rank p]}
 
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int64_t i0 = static_cast<int64_t>(blockIdx.x) * BI;
@@ -91,36 +97,46 @@ db_partial_kernel(const uint8_t* __restrict__ dyq, const uint16_t* __restrict__ 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
 
-    for (int64_t t0 = t_begin; t0 < t_end; t0 += BT) {
-        __syncthreads();                       // the previous step's operand reads are done
-        // dyq tile: BT rows x BI bytes = 16 KB = 16 wave instructions of 1 KB (8 token rows each)
+    for (int64_t tg = t_begin; tg < t_end; tg += kTiles * BT) {
+        __syncthreads();                       // the previous group's operand reads are done
+        // dyq tiles: BT rows x BI bytes = 16 KB = 16 wave instructions of 1 KB (8 token rows each).
+        // Rows, features and whole tiles out of range are fetched from a block of zeros.
 #pragma unroll
-        for (int it = 0; it < BT * BI / 1024 / 4; ++it) {
-            const int q = it * 4 + wave;
-            const int trow = q * 8 + (lane >> 3);
-            const int c = (lane & 7) ^ swz_t<CH_DY>(trow);
-            const int64_t gt = t0 + trow, gi = i0 + c * 16;
-            const uint8_t* src = (gt < t_end && gi < m) ? dyq + gt * m + gi : g_zero16;
-            __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(s_dy + q * 1024), 16, 0, 0);
+        for (int tl = 0; tl < kTiles; ++tl) {
+            const int64_t t0 = tg + tl * BT;
+#pragma unroll
+            for (int it = 0; it < BT * BI / 1024 / 4; ++it) {
+                const int q = it * 4 + wave;
+                const int trow = q * 8 + (lane >> 3);
+                const int c = (lane & 7) ^ swz_t<CH_DY>(trow);
+                const int64_t gt = t0 + trow, gi = i0 + c * 16;
+                const uint8_t* src = (gt < t_end && gi < m) ? dyq + gt * m + gi : g_zero16;
+                __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(s_tiles + tl * kTileBytes + q * 1024), 16, 0, 0);
+            }
         }
-        // O_A tile: BT rows x BP bf16 -> E4M3 bytes.  256 threads x 32 values: thread -> (row, half row)
-        {
-            const int trow = threadIdx.x >> 1, half = threadIdx.x & 1;     // 32 ranks per half
-            const int64_t gt = t0 + trow;
-            uint32_t codes[8];
-            uint4 w[4];
-            // rows and ranks out of range read a block of zeros (address select: a load inside a
-            // branch would be waited for at the join and serialise the four loads)
+        // O_A tiles: BT rows x BP bf16 -> E4M3 bytes.  256 threads x 32 values: thread -> (row, half row)
+        const int trow = threadIdx.x >> 1, half = threadIdx.x & 1;         // 32 ranks per half
+        uint4 w[kTiles][4];
+        // rows and ranks out of range read a block of zeros (address select: a load inside a
+        // branch would be waited for at the join and serialise the loads)
+#pragma unroll
+        for (int tl = 0; tl < kTiles; ++tl) {
+            const int64_t gt = tg + tl * BT + trow;
 #pragma unroll
             for (int v8 = 0; v8 < 4; ++v8) {                               // 8 bf16 per 16-byte load
                 const int64_t gp = p0 + half * 32 + v8 * 8;
                 const void* src = (gt < t_end && gp < r) ? static_cast<const void*>(o_a + gt * r + gp)
                                                          : static_cast<const void*>(g_zero16);
-                w[v8] = *reinterpret_cast<const uint4*>(src);
+                w[tl][v8] = *reinterpret_cast<const uint4*>(src);
             }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int tl = 0; tl < kTiles; ++tl) {
+            uint32_t codes[8];
 #pragma unroll
             for (int v8 = 0; v8 < 4; ++v8) {
-                const uint32_t ww[4] = {w[v8].x, w[v8].y, w[v8].z, w[v8].w};
+                const uint32_t ww[4] = {w[tl][v8].x, w[tl][v8].y, w[tl][v8].z, w[tl][v8].w};
                 float f[8];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -130,6 +146,7 @@ db_partial_kernel(const uint8_t* __restrict__ dyq, const uint16_t* __restrict__ 
                 codes[2 * v8] = cast4_e4m3(f[0], f[1], f[2], f[3]);
                 codes[2 * v8 + 1] = cast4_e4m3(f[4], f[5], f[6], f[7]);
             }
+            uint8_t* s_oa = s_tiles + tl * kTileBytes + BT * BI;
 #pragma unroll
             for (int c = 0; c < 2; ++c) {                                   // two 16-byte chunks
                 const int chunk = (half * 2 + c) ^ swz_t<CH_OA>(trow);
@@ -142,13 +159,19 @@ db_partial_kernel(const uint8_t* __restrict__ dyq, const uint16_t* __restrict__ 
         __syncthreads();
         // wave w owns features [32 w, 32 w + 32) of the tile and both 32-wide rank blocks
 #pragma unroll
-        for (int kh = 0; kh < 2; ++kh) {
-            const v8i a = read_tokens_of_feature<CH_DY>(s_dy, wave * 32, kh, lane);
+        for (int tl = 0; tl < kTiles; ++tl) {
+            if (tg + tl * BT >= t_end) break;                               // tiles beyond the range hold zeros
+            const uint8_t* s_dy = s_tiles + tl * kTileBytes;
+            const uint8_t* s_oa = s_dy + BT * BI;
 #pragma unroll
-            for (int b = 0; b < 2; ++b) {
-                const v8i bb = read_tokens_of_feature<CH_OA>(s_oa, b * 32, kh, lane);
-                acc[b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bb, acc[b], 1 /* E5M2 */, 0 /* E4M3 */,
-                                                                          0, 0, 0, 0);
+            for (int kh = 0; kh < 2; ++kh) {
+                const v8i a = read_tokens_of_feature<CH_DY>(s_dy, wave * 32, kh, lane);
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    const v8i bb = read_tokens_of_feature<CH_OA>(s_oa, b * 32, kh, lane);
+                    acc[b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bb, acc[b], 1 /* E5M2 */, 0 /* E4M3 */,
+                                                                              0, 0, 0, 0);
+                }
             }
         }
     }
@@ -212,7 +235,7 @@ db_reduce_kernel(const float* __restrict__ partial, int64_t count,
 int db_splits(int64_t T, int64_t m)
 {
     const int64_t i_tiles = (m + BI - 1) / BI;
-    int64_t splits = (512 + i_tiles - 1) / i_tiles;          // aim at ~2 workgroups per CU
+    int64_t splits = (384 + i_tiles - 1) / i_tiles;          // aim at one to two workgroups per CU
     const int64_t max_by_tokens = (T + BT - 1) / BT;
     if (splits > max_by_tokens) splits = max_by_tokens;
     if (splits > kDbSplitMax) splits = kDbSplitMax;
@@ -230,9 +253,12 @@ hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, con
     tps = (tps + BT - 1) / BT * BT;
     const dim3 grid(static_cast<unsigned>((m + BI - 1) / BI), static_cast<unsigned>(splits),
                     static_cast<unsigned>((r + BP - 1) / BP));
-    db_partial_kernel<<<grid, kThreads, 0, stream>>>(dyq, static_cast<const uint16_t*>(o_a), amax_oa, T, m, r, tps,
-                                                     partials);
-    hipError_t e = hipGetLastError();
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&db_partial_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kDbLdsBytes));
+    if (e != hipSuccess) return e;
+    db_partial_kernel<<<grid, kThreads, kDbLdsBytes, stream>>>(dyq, static_cast<const uint16_t*>(o_a), amax_oa, T, m, r,
+                                                               tps, partials);
+    e = hipGetLastError();
     if (e != hipSuccess) return e;
     const int64_t count = m * r;
     int64_t blocks = (count / 4 + kThreads - 1) / kThreads;
