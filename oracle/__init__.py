@@ -44,6 +44,12 @@ def lib():
         L.orc_db.argtypes = [p, c.c_float, p, c.c_float, c.c_int64, c.c_int64, c.c_int64,
                              p, c.c_int64, p, p, p]
         L.orc_delta_accumulate.argtypes = [p, p, c.c_int64, c.c_float]
+        L.orc_adamw_delta.argtypes = [p, p, p, p, c.c_int64, c.c_int64, c.c_double, c.c_double, c.c_double,
+                                      c.c_double, c.c_double]
+        L.orc_sum_squares.restype = c.c_double
+        L.orc_sum_squares.argtypes = [p, c.c_int64]
+        L.orc_clip_coef.restype = c.c_double
+        L.orc_clip_coef.argtypes = [c.c_double, c.c_double]
         L.orc_row_scores.argtypes = [p, c.c_int64, c.c_int64, p]
         L.orc_topk_rows.argtypes = [p, c.c_int64, c.c_int64, p]
         L.orc_proxy_update.argtypes = [p, p, c.c_int64, c.c_int64, c.c_int64, c.c_int64, p, c.c_int]
@@ -157,6 +163,27 @@ def delta_accumulate(buf, d_b, lr) -> np.ndarray:
     assert b.shape == g.shape
     lib().orc_delta_accumulate(_ptr(b), _ptr(g), b.size, float(lr))
     return b
+
+
+def adamw_delta(d_b, exp_avg, exp_avg_sq, buf, step, lr=2e-4, beta1=0.9, beta2=0.999, eps=1e-8, clip_coef=1.0):
+    """One optimizer step into the proxy buffer; returns new (exp_avg, exp_avg_sq, buf), all fp32."""
+    g = _c(d_b, np.float32)
+    m = np.array(exp_avg, np.float32, copy=True)
+    v = np.array(exp_avg_sq, np.float32, copy=True)
+    b = np.array(buf, np.float32, copy=True)
+    assert g.shape == m.shape == v.shape == b.shape
+    lib().orc_adamw_delta(_ptr(g), _ptr(m), _ptr(v), _ptr(b), g.size, int(step), float(lr), float(beta1),
+                          float(beta2), float(eps), float(clip_coef))
+    return m, v, b
+
+
+def sum_squares(g) -> float:
+    a = _c(g, np.float32)
+    return float(lib().orc_sum_squares(_ptr(a), a.size))
+
+
+def clip_coef(sum_sq: float, max_norm: float = 0.3) -> float:
+    return float(lib().orc_clip_coef(float(sum_sq), float(max_norm)))
 
 
 def row_scores(buf) -> np.ndarray:

@@ -283,6 +283,54 @@ void orc_delta_accumulate(float* buf, const double* d_b, int64_t count, float lr
 }
 
 /* ------------------------------------------------------------------------- */
+/* Optimizer step into the proxy buffer: "DeltaBuffer <- Optimizer(dB, lr)"   */
+/* of the backward-and-update algorithm with the optimizer the experiments    */
+/* name (AdamW, maximum gradient norm 0.3; "Detailed experimental settings"). */
+/* B itself is never stored, only its change, so the decoupled weight decay   */
+/* has nothing to act on and is taken as zero (the default of the recipe the  */
+/* paper follows); the step is then Adam with bias correction:                */
+/*   g   = c * dB                       c = clip coefficient (below)          */
+/*   m   = b1*m + (1-b1)*g              v = b2*v + (1-b2)*g*g                 */
+/*   dlt = -(lr / (1-b1^t)) * m / ( sqrt(v)/sqrt(1-b2^t) + eps )              */
+/*   buf = buf + dlt                                                          */
+/* Each element is formed in fp64 from the fp32 state and rounded to fp32     */
+/* when stored (moments and buffer are fp32 arrays).                          */
+/* ------------------------------------------------------------------------- */
+void orc_adamw_delta(const float* d_b, float* exp_avg, float* exp_avg_sq, float* buf, int64_t count,
+                     int64_t step, double lr, double beta1, double beta2, double eps, double clip_coef)
+{
+    double bias1 = 1.0 - pow(beta1, (double)step);
+    double bias2 = 1.0 - pow(beta2, (double)step);
+    for (int64_t e = 0; e < count; ++e) {
+        double g = clip_coef * (double)d_b[e];
+        double m = beta1 * (double)exp_avg[e] + (1.0 - beta1) * g;
+        double v = beta2 * (double)exp_avg_sq[e] + (1.0 - beta2) * g * g;
+        double denom = sqrt(v) / sqrt(bias2) + eps;
+        double dlt = -(lr / bias1) * m / denom;
+        exp_avg[e] = (float)m;
+        exp_avg_sq[e] = (float)v;
+        buf[e] = (float)((double)buf[e] + dlt);
+    }
+}
+
+/* Sum of squares of a gradient tensor in fp64, elements in index order: one   */
+/* term of the global gradient norm.                                           */
+double orc_sum_squares(const float* g, int64_t count)
+{
+    double s = 0.0;
+    for (int64_t e = 0; e < count; ++e) s += (double)g[e] * (double)g[e];
+    return s;
+}
+
+/* Clip coefficient of gradient-norm clipping over all adapter gradients:      */
+/* total = sqrt(sum of squares of every gradient), c = min(1, max/(total+1e-6)) */
+double orc_clip_coef(double sum_squares, double max_norm)
+{
+    double c = max_norm / (sqrt(sum_squares) + 1e-6);
+    return c < 1.0 ? c : 1.0;
+}
+
+/* ------------------------------------------------------------------------- */
 /* Row-wise proxy update (update equation; last two lines of the backward-    */
 /* and-update algorithm):                                                     */
 /*   score_i = sum_p |buf[i,p]|            fp64, p ascending                  */
