@@ -207,6 +207,12 @@ def main():
     ms_gemm_fwd = _time_region(lambda: fq.fp8_gemm(layer.xq, fq.E4M3, layer.wq[:m], False, layer.s_x, layer.s_w, y_tmp), it)
     ms_gemm_dx = _time_region(lambda: fq.fp8_gemm(layer.dyq, fq.E5M2, layer.wq[:m], True, layer.s_dy, layer.s_w,
                                                   layer.dx), it)
+    # optimizer variant of the buffer step: bwd without the SGD step, global-norm term, AdamW into the buffer
+    sum_sq = torch.zeros(1, dtype=torch.float64, device="cuda")
+    layer.adamw_step(1, sum_sq)                       # allocates the moments
+    ms_sqnorm = _time_region(lambda: fq.grad_sqnorm(layer.d_b, sum_sq, layer.ws), it)
+    ms_adamw = _time_region(lambda: layer.adamw_step(2, sum_sq), it)
+    layer.delta_buf.zero_()
     s_tmp = torch.zeros(1, device="cuda")
     ms_quant = _time_region(lambda: fq.quantize(x, fq.E4M3, layer.xq, s_tmp, layer.ws), it)
     del y_tmp
@@ -236,6 +242,9 @@ def main():
         "proxy_update": {"ms": ms_upd, "GB/s": upd_bytes / (ms_upd * 1e-3) / 1e9,
                          "frac_hbm_peak": upd_bytes / (ms_upd * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "note": "three dependent launches over 1.6 MB: latency bound"},
+        "adamw_buffer_step": {"grad_sqnorm_ms": ms_sqnorm, "adamw_delta_ms": ms_adamw,
+                              "bytes": 28.0 * m * r, "GB/s": 28.0 * m * r / (ms_adamw * 1e-3) / 1e9,
+                              "note": "optional replacement of the SGD buffer step inside melded_bwd; not in the timed step"},
         "calls": {"melded_fwd_ms": ms_fwd, "melded_bwd_ms": ms_bwd, "proxy_update_ms": ms_upd},
         "gemm_flops": {"fwd_backbone": flops_fwd, "fwd_adapter": 2.0 * T * n * r, "dx": flops_dx, "db": flops_db},
     }

@@ -11,6 +11,9 @@
  *                        dB = dY~^T O_A, optional proxy-buffer step
  *   falqon_proxy_update  row scores of the proxy buffer, top-k rows, requantize-and-
  *                        write of those rows of W~
+ * and, between the last two, the optimizer step that fills the proxy buffer
+ * (falqon_grad_sqnorm, falqon_adamw_delta) in place of the plain SGD step that
+ * falqon_melded_bwd can apply itself.
  *
  * Conventions (all calls)
  *   - Orientation is row-major with tokens first: X[T,n], W~'[(m+r),n], Y[T,m],
@@ -174,6 +177,42 @@ falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int6
 falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t* b, int b_is_kn,
                               int64_t M, int64_t N, int64_t K, const float* s_a, const float* s_b,
                               void* c, falqon_dtype ct, void* stream);
+
+/*
+ * Optimizer step into the proxy buffer: "DeltaBuffer <- Optimizer(dL/dB, lr)", the second line of
+ * the loop of the paper's backward-and-update algorithm, with the optimizer its experiments name
+ * (AdamW with a maximum gradient norm of 0.3; "Detailed experimental settings").  Two calls:
+ *
+ * falqon_grad_sqnorm adds the sum of squares of one gradient tensor to a device accumulator, in
+ * fp64 and in a fixed order (bitwise reproducible).  Called once per layer on a zeroed
+ * accumulator it yields the squared global gradient norm that clipping needs.
+ *
+ *   g        in      fp32 [count], count a multiple of 4
+ *   sum_sq   in/out  device double, incremented
+ *   ws       scratch of at least 4096 bytes
+ *
+ * falqon_adamw_delta performs, element by element in fp32,
+ *   g = c * dB,  c = min(1, max_norm / (sqrt(*sum_sq) + 1e-6))   (c = 1 when sum_sq is NULL)
+ *   exp_avg    = beta1 * exp_avg    + (1 - beta1) * g
+ *   exp_avg_sq = beta2 * exp_avg_sq + (1 - beta2) * g * g
+ *   delta_buf += -(lr / (1 - beta1^step)) * exp_avg / (sqrt(exp_avg_sq) / sqrt(1 - beta2^step) + eps)
+ * B itself is never stored (the buffer holds only its change), so there is no decoupled weight
+ * decay term.  Use it with falqon_melded_bwd called with delta_buf = NULL.
+ *
+ *   d_b         in      fp32 [m, r]
+ *   exp_avg, exp_avg_sq  in/out  fp32 [m, r], zero before the first step
+ *   delta_buf   in/out  fp32 [m, r]
+ *   lr, beta1, beta2, eps, max_norm  host doubles; 1 - beta and the bias corrections are formed in
+ *               double on the host and handed to the kernel as fp32 factors
+ *   step        1-based count of optimizer steps taken, this one included
+ *   sum_sq      in      device double (squared global gradient norm) or NULL for no clipping
+ * Errors: FALQON_ERR_SHAPE also for step < 1, betas outside [0, 1), eps <= 0 or max_norm <= 0.
+ */
+falqon_status falqon_grad_sqnorm(const float* g, int64_t count, double* sum_sq,
+                                 void* ws, size_t ws_bytes, void* stream);
+falqon_status falqon_adamw_delta(const float* d_b, float* exp_avg, float* exp_avg_sq, float* delta_buf,
+                                 int64_t m, int64_t r, int64_t step, double lr, double beta1, double beta2,
+                                 double eps, const double* sum_sq, double max_norm, void* stream);
 
 #ifdef __cplusplus
 }

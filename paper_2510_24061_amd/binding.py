@@ -56,6 +56,11 @@ def lib():
         L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
         L.falqon_fp8_gemm.restype = c.c_int
         L.falqon_fp8_gemm.argtypes = [vp, c.c_int, vp, c.c_int, i64, i64, i64, f32p, f32p, vp, c.c_int, vp]
+        L.falqon_grad_sqnorm.restype = c.c_int
+        L.falqon_grad_sqnorm.argtypes = [f32p, i64, vp, vp, c.c_size_t, vp]
+        L.falqon_adamw_delta.restype = c.c_int
+        L.falqon_adamw_delta.argtypes = [f32p, f32p, f32p, f32p, i64, i64, i64, c.c_double, c.c_double, c.c_double,
+                                         c.c_double, vp, c.c_double, vp]
         _lib = L
     return _lib
 
@@ -141,6 +146,25 @@ def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c) -> None:
     _check(st, "falqon_fp8_gemm")
 
 
+def grad_sqnorm(g, sum_sq, ws) -> None:
+    """*sum_sq (device fp64 scalar) += sum of squares of g (fp32)."""
+    _dev(g, sum_sq, ws)
+    st = lib().falqon_grad_sqnorm(_p(g), g.numel(), _p(sum_sq), _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_grad_sqnorm")
+
+
+def adamw_delta(d_b, exp_avg, exp_avg_sq, delta_buf, step: int, lr: float = 2e-4, beta1: float = 0.9,
+                beta2: float = 0.999, eps: float = 1e-8, sum_sq=None, max_norm: float = 0.3) -> None:
+    """AdamW step on the (clipped) adapter gradient, written into the proxy buffer."""
+    _dev(d_b, exp_avg, exp_avg_sq, delta_buf)
+    if sum_sq is not None:
+        _dev(sum_sq)
+    m, r = d_b.shape
+    st = lib().falqon_adamw_delta(_p(d_b), _p(exp_avg), _p(exp_avg_sq), _p(delta_buf), m, r, int(step), lr, beta1,
+                                  beta2, eps, _p(sum_sq) if sum_sq is not None else None, max_norm, _stream())
+    _check(st, "falqon_adamw_delta")
+
+
 class MeldedLinear:
     """Buffers of one melded layer plus the four calls, for tests and the benchmark.
 
@@ -185,6 +209,15 @@ class MeldedLinear:
         melded_bwd(dy, self.wq, self.s_w, self.o_a, self.amax_oa, self.n, self.r, self.dyq, self.s_dy, self.dx,
                    self.d_b, self.delta_buf if accumulate else None, lr, self.ws)
         return self.dx
+
+    def adamw_step(self, step: int, sum_sq: Optional[torch.Tensor] = None, lr: float = 2e-4, beta1: float = 0.9,
+                   beta2: float = 0.999, eps: float = 1e-8, max_norm: float = 0.3) -> None:
+        """DeltaBuffer <- AdamW(d_b) (after backward(accumulate=False)); moments are allocated on first use."""
+        if not hasattr(self, "exp_avg"):
+            self.exp_avg = torch.zeros_like(self.d_b)
+            self.exp_avg_sq = torch.zeros_like(self.d_b)
+        adamw_delta(self.d_b, self.exp_avg, self.exp_avg_sq, self.delta_buf, step, lr, beta1, beta2, eps, sum_sq,
+                    max_norm)
 
     def update(self, clear_selected: bool = True) -> torch.Tensor:
         proxy_update(self.delta_buf, self.wq, self.m, self.r, self.k, self.idx, self.ws, clear_selected)

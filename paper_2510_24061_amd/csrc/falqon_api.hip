@@ -1,5 +1,7 @@
 // C ABI of libfalqon: argument validation on the host, then kernel launches on the caller's
 // stream.  Nothing here allocates, synchronises or keeps state.
+#include <cmath>
+
 #include "falqon_internal.h"
 
 namespace falqon {
@@ -234,6 +236,43 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
     g.c0 = c; g.ldc0 = N; g.c0_is_f32 = (ct == FALQON_F32); g.n_split = N;
     g.c1 = nullptr; g.ldc1 = 0; g.amax1 = nullptr;
     hipError_t e = launch_gemm(g, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+falqon_status falqon_grad_sqnorm(const float* g, int64_t count, double* sum_sq,
+                                 void* ws, size_t ws_bytes, void* stream)
+{
+    if (count < 4 || (count % 4) || count > (int64_t(1) << 40)) return FALQON_ERR_SHAPE;
+    if (!g || !sum_sq) return FALQON_ERR_NULL;
+    if (misaligned(g) || (reinterpret_cast<uintptr_t>(sum_sq) & 7u)) return FALQON_ERR_ALIGN;
+    if (!ws || ws_bytes < 4096) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    hipError_t e = launch_grad_sqnorm(g, count, sum_sq, static_cast<double*>(ws), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+falqon_status falqon_adamw_delta(const float* d_b, float* exp_avg, float* exp_avg_sq, float* delta_buf,
+                                 int64_t m, int64_t r, int64_t step, double lr, double beta1, double beta2,
+                                 double eps, const double* sum_sq, double max_norm, void* stream)
+{
+    if (m < 16 || r < 16 || (m % 16) || (r % 16) || r > 256 || m > (int64_t(1) << 20)) return FALQON_ERR_SHAPE;
+    if (step < 1 || !(beta1 >= 0.0 && beta1 < 1.0) || !(beta2 >= 0.0 && beta2 < 1.0) || !(eps > 0.0))
+        return FALQON_ERR_SHAPE;
+    if (sum_sq && !(max_norm > 0.0)) return FALQON_ERR_SHAPE;
+    if (!d_b || !exp_avg || !exp_avg_sq || !delta_buf) return FALQON_ERR_NULL;
+    if (misaligned(d_b) || misaligned(exp_avg) || misaligned(exp_avg_sq) || misaligned(delta_buf) ||
+        (reinterpret_cast<uintptr_t>(sum_sq) & 7u))
+        return FALQON_ERR_ALIGN;
+    // 1 - beta and the bias corrections in double on the host, handed over as fp32 factors
+    AdamFactors f;
+    f.beta1 = static_cast<float>(beta1); f.one_minus_beta1 = static_cast<float>(1.0 - beta1);
+    f.beta2 = static_cast<float>(beta2); f.one_minus_beta2 = static_cast<float>(1.0 - beta2);
+    f.eps = static_cast<float>(eps);
+    f.step_size = static_cast<float>(lr / (1.0 - pow(beta1, static_cast<double>(step))));
+    f.inv_sqrt_bias2 = static_cast<float>(1.0 / sqrt(1.0 - pow(beta2, static_cast<double>(step))));
+    f.max_norm = max_norm;
+    hipError_t e = launch_adamw_delta(d_b, exp_avg, exp_avg_sq, delta_buf, m * r, f, sum_sq,
+                                      static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 

@@ -67,4 +67,16 @@ hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t
                                int32_t* idx_out, int clear_selected, double* scores, float* delta_sel,
                                hipStream_t stream);
 
+// ---- optimizer step into the proxy buffer (optimizer.hip) ------------------------------------
+// partials: at least 256 doubles of scratch
+hipError_t launch_grad_sqnorm(const float* g, int64_t count, double* sum_sq, double* partials, hipStream_t stream);
+struct AdamFactors {
+    float beta1, one_minus_beta1, beta2, one_minus_beta2, eps;
+    float step_size;         // lr / (1 - beta1^t)
+    float inv_sqrt_bias2;    // 1 / sqrt(1 - beta2^t)
+    double max_norm;
+};
+hipError_t launch_adamw_delta(const float* d_b, float* exp_avg, float* exp_avg_sq, float* delta_buf, int64_t count,
+                              const AdamFactors& f, const double* sum_sq, hipStream_t stream);
+
 }  // namespace falqon

@@ -114,3 +114,26 @@ def test_product_path_never_imports_the_oracle():
                 text = open(os.path.join(dirpath, fn)).read()
                 assert "import oracle" not in text and "from oracle" not in text, fn
                 assert "falqon_oracle" not in text and "orc_" not in text, fn
+
+
+def test_optimizer_argument_validation(L):
+    import paper_2510_24061_amd as fq
+    fq.lib()
+    ok, odd = 0x10000, 0x10004
+    n = L.falqon_grad_sqnorm
+    assert n(None, 64, _vp(ok), _vp(ok), 4096, None) == 1
+    assert n(_vp(ok), 64, None, _vp(ok), 4096, None) == 1
+    assert n(_vp(ok), 0, _vp(ok), _vp(ok), 4096, None) == 2 and n(_vp(ok), 66, _vp(ok), _vp(ok), 4096, None) == 2
+    assert n(_vp(odd), 64, _vp(ok), _vp(ok), 4096, None) == 3 and n(_vp(ok), 64, _vp(odd), _vp(ok), 4096, None) == 3
+    assert n(_vp(ok), 64, _vp(ok), None, 4096, None) == 5 and n(_vp(ok), 64, _vp(ok), _vp(ok), 100, None) == 5
+
+    a = L.falqon_adamw_delta
+
+    def adam(d_b=ok, m1=ok, m2=ok, buf=ok, m=64, r=16, step=1, lr=2e-4, b1=0.9, b2=0.999, eps=1e-8, ss=None,
+             mx=0.3):
+        return a(_vp(d_b), _vp(m1), _vp(m2), _vp(buf), m, r, step, lr, b1, b2, eps, _vp(ss), mx, None)
+
+    assert adam(d_b=None) == 1 and adam(m1=None) == 1 and adam(m2=None) == 1 and adam(buf=None) == 1
+    assert adam(m=0) == 2 and adam(r=8) == 2 and adam(r=512) == 2 and adam(step=0) == 2
+    assert adam(b1=1.0) == 2 and adam(b2=-0.1) == 2 and adam(eps=0.0) == 2 and adam(ss=ok, mx=0.0) == 2
+    assert adam(buf=odd) == 3 and adam(ss=odd) == 3
