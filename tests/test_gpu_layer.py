@@ -286,3 +286,36 @@ def test_full_size_config_sampled(cfg, layer):
     assert np.array_equal(np_of(layer_gpu.idx), idx_ref)
     assert np.array_equal(np_of(layer_gpu.wq), w_ref)
     assert np_of(layer_gpu.delta_buf).tobytes() == buf_ref.tobytes()
+
+
+def _random_shapes(count, seed):
+    """Seeded shapes that mix every tile path: ragged T, n and m not multiples of the K step or
+    the tile sizes, all adapter widths, both tile configurations."""
+    g = np.random.default_rng(seed)
+    shapes = []
+    for i in range(count):
+        big = i % 4 == 0                                   # every fourth case is large enough for 256x256 tiles
+        T = int(g.integers(1, 700)) if not big else int(g.integers(2049, 3200))
+        n = 16 * int(g.integers(1, 40)) if not big else 16 * int(g.integers(8, 48))
+        m = 16 * int(g.integers(1, 60)) if not big else 16 * int(g.integers(140, 260))
+        r = 16 * int(g.choice([1, 1, 2, 3, 4, 4, 5, 8, 16]))
+        k = int(g.integers(1, min(m, 40) + 1))
+        shapes.append((T, n, m, r, k))
+    return shapes
+
+
+@pytest.mark.parametrize("shape", _random_shapes(16, seed=2510))
+def test_random_shapes_forward_backward_update(shape):
+    T, n, m, r, k = shape
+    print(f"random shape T={T} n={n} m={m} r={r} k={k}", flush=True)
+    d, wcat, s_w = _inputs(T, n, m, r, outliers=(T % 2 == 0), seed=7000 + T + n)
+    _check_forward(T, n, m, r, k, d, wcat, s_w, torch.bfloat16, n_sample=40)
+    _check_backward(T, n, m, r, k, d, wcat, s_w, torch.float32, n_sample=40)
+    buf = workloads.make_delta_buffer(m, r, seed=T, scale=5e-3, ties=True)
+    layer = layer_on_gpu(T, n, m, r, k, wcat, s_w)
+    layer.delta_buf.copy_(buf)
+    layer.update()
+    torch.cuda.synchronize()
+    idx_ref, w_ref, buf_ref = oracle.proxy_update(buf.numpy(), wcat, m, r, k)
+    assert np.array_equal(np_of(layer.idx), idx_ref) and np.array_equal(np_of(layer.wq), w_ref)
+    assert np_of(layer.delta_buf).tobytes() == buf_ref.tobytes()
