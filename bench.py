@@ -152,12 +152,72 @@ def separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, iters):
     return _time_region(step, iters)
 
 
+def run_stack(fq, cfg, args):
+    """Configs with several layers: every projection of the config as its own melded layer (own
+    weights, buffer and saved O_A; per-step activations shared between layers of one shape, which
+    run one after the other).  A step is forward over all layers, backward over all layers in
+    reverse; the proxy update of every layer follows each `accumulate_steps`-th step."""
+    T, r, k = cfg.T, cfg.r, cfg.k
+    layers, inputs = [], []
+    for li, shape in enumerate(cfg.layers):
+        d = workloads.config_layer_inputs(cfg.cfg, li)
+        w, a = d["w"].cuda(), d["a"].cuda()
+        first = None
+        for _ in range(shape.count):
+            layer = fq.MeldedLinear(T, shape.n, shape.m, r, k, out_dtype=torch.bfloat16, share_transients_with=first)
+            layer.init_weights(w, a)
+            first = first or layer
+            layers.append(layer)
+            inputs.append(li)
+        del w, a
+    xs = [workloads.config_layer_inputs(cfg.cfg, li)["x"].cuda() for li in range(len(cfg.layers))]
+    dys = [workloads.config_layer_inputs(cfg.cfg, li)["dy"].cuda() for li in range(len(cfg.layers))]
+    acc = cfg.accumulate_steps
+
+    def train_step(i):
+        for layer, li in zip(layers, inputs):
+            layer.forward(xs[li])
+        for layer, li in zip(reversed(layers), reversed(inputs)):
+            layer.backward(dys[li], lr=cfg.lr)
+        if (i + 1) % acc == 0:
+            for layer in layers:
+                layer.update()
+
+    warm = max(args.warmup, acc) // acc * acc
+    steps = max(args.steps, acc) // acc * acc                      # whole accumulation cycles
+    for i in range(warm):
+        train_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        train_step(i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    flops = sum(s.count * (2.0 * T * s.n * (s.m + r) + 2.0 * T * s.m * s.n + 2.0 * T * s.m * r) for s in cfg.layers)
+    n_layers = len(layers)
+    desc = ", ".join(f"{s.count}x {s.m}x{s.n}" for s in cfg.layers)
+    out = {
+        "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+        "steps": steps, "warmup": warm, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "fp8 (E4M3 weights/activations, E5M2 gradients), fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": f"config {cfg.cfg} ({cfg.name}): T={T}, {n_layers} layers ({desc}), r={r}, k={k}; "
+                               f"fwd + bwd over all layers per step, proxy update of every layer each "
+                               f"{acc} step(s) (its time is spread over them)"},
+        "roofline": {"bound": "mfma", "kernel": "all FP8 GEMMs of the step (whole-step time, not a kernel time)",
+                     "achieved": flops / (ms_per_step * 1e-3) / 1e12, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / (ms_per_step * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, "traffic": None},
+        "kernels": {"gemm_flops_per_step": flops, "layers": n_layers},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload (2 = the headline LLaMA-7B attention projection)")
+    ap.add_argument("--config", type=int, default=2, help="workload (2 = the headline LLaMA-7B attention projection; 3-5 run all their layers as a stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
                     help="skip the bf16 LoRA and separate-path FP8 LoRA comparison layers (profiling runs: their "
@@ -175,6 +235,9 @@ def main():
     import paper_2510_24061_amd as fq
 
     cfg = workloads.CONFIGS[args.config]
+    if sum(s.count for s in cfg.layers) > 1:
+        run_stack(fq, cfg, args)
+        return
     d = workloads.config_layer_inputs(args.config, 0)
     m, n, r, k, T = d["shape"].m, d["shape"].n, cfg.r, cfg.k, cfg.T
     layer = fq.MeldedLinear(T, n, m, r, k, out_dtype=torch.bfloat16)

@@ -172,23 +172,32 @@ class MeldedLinear:
     Everything else is per-step output or scratch.  All memory is allocated once here.
     """
 
-    def __init__(self, T: int, n: int, m: int, r: int, k: int, out_dtype=torch.bfloat16, device="cuda"):
+    def __init__(self, T: int, n: int, m: int, r: int, k: int, out_dtype=torch.bfloat16, device="cuda",
+                 share_transients_with: Optional["MeldedLinear"] = None):
+        """share_transients_with: another layer of the same shape whose per-step buffers (x~, y, dy~,
+        dx, workspace) this one aliases; for stacks whose layers run one after the other."""
         self.T, self.n, self.m, self.r, self.k = T, n, m, r, k
         dev = torch.device(device)
         u8, f32 = torch.uint8, torch.float32
         self.wq = torch.zeros(m + r, n, dtype=u8, device=dev)
         self.s_w = torch.zeros(1, dtype=f32, device=dev)
         self.delta_buf = torch.zeros(m, r, dtype=f32, device=dev)
+        self.o_a = torch.empty(T, r, dtype=torch.bfloat16, device=dev)
+        self.amax_oa = torch.zeros(1, dtype=f32, device=dev)
+        self.d_b = torch.empty(m, r, dtype=f32, device=dev)
+        self.idx = torch.zeros(k, dtype=torch.int32, device=dev)
+        o = share_transients_with
+        if o is not None:
+            if (o.T, o.n, o.m, o.r) != (T, n, m, r) or o.y.dtype != out_dtype:
+                raise ValueError("transient buffers can only be shared between layers of one shape")
+            self.xq, self.s_x, self.y, self.dyq, self.s_dy, self.dx, self.ws = o.xq, o.s_x, o.y, o.dyq, o.s_dy, o.dx, o.ws
+            return
         self.xq = torch.empty(T, n, dtype=u8, device=dev)
         self.s_x = torch.zeros(1, dtype=f32, device=dev)
         self.y = torch.empty(T, m, dtype=out_dtype, device=dev)
-        self.o_a = torch.empty(T, r, dtype=torch.bfloat16, device=dev)
-        self.amax_oa = torch.zeros(1, dtype=f32, device=dev)
         self.dyq = torch.empty(T, m, dtype=u8, device=dev)
         self.s_dy = torch.zeros(1, dtype=f32, device=dev)
         self.dx = torch.empty(T, n, dtype=out_dtype, device=dev)
-        self.d_b = torch.empty(m, r, dtype=f32, device=dev)
-        self.idx = torch.zeros(k, dtype=torch.int32, device=dev)
         nbytes = workspace_bytes(T, n, m, r)
         if nbytes == 0:
             raise ValueError("invalid layer shape")
