@@ -119,8 +119,9 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
 
     // O_merged <- x~ W~'^T / (s_w s_x), split into y and O_A.  When the r adapter columns fit
     // into the last, partly empty tile column of the backbone product they ride along in the one
-    // GEMM; otherwise they would add a whole, almost empty tile column (a second wave over the
-    // CUs), and are formed by the skinny kernel from the same x~ instead.
+    // GEMM, whose epilogue splits them off; otherwise they would add a whole, almost empty tile
+    // column (a second round over the CUs) and are formed from the same x~ by a split-K launch of
+    // the same kernel on the adapter rows instead.
     const int64_t tile = gemm_tile_n(T, m + r);
     const bool merged = (m + r + tile - 1) / tile == (m + tile - 1) / tile;
     GemmArgs g;

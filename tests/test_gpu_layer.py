@@ -25,13 +25,13 @@ SHAPES = [
     (300, 1024, 1040, 64, 32, True),      # m + r = 1104: four and a bit 256-wide tiles
     (520, 272, 528, 32, 16, True),        # K tails: n = 272 and m = 528 are not multiples of 128
     (2100, 1024, 4112, 48, 12, True),     # enough tiles for the 256x256 path, ragged tails
-    (130, 256, 256, 160, 8, False),       # wide adapter: five 32-column blocks in the skinny product
+    (130, 256, 256, 160, 8, False),       # wide adapter: five 32-column blocks in the adapter product
     (64, 128, 512, 256, 4, False),        # largest rank
-    # adapter columns formed in the quantizer's cast pass (they would start a tile column of their own)
+    # adapter columns that would start a tile column of their own (separate split-K launch)
     (100, 336, 384, 48, 8, True),         # ragged rows, K = 2 chunks of 128 and a tail of 80
-    (50, 2176, 256, 64, 8, False),        # widest adapter of that path, 17 K chunks over 16 waves
+    (50, 2176, 256, 64, 8, False),        # K = 17 steps of 128
     (33, 640, 128, 32, 4, False),
-    (40, 384, 128, 96, 4, False),         # wider than that: split-K launch
+    (40, 384, 128, 96, 4, False),
 ]
 
 
@@ -80,9 +80,9 @@ def test_forward(shape, out_dtype):
 
 
 @pytest.mark.parametrize("T,n,m,r", [(300, 256, 272, 16),     # adapter columns inside the backbone GEMM
-                                     (300, 400, 256, 48),     # ... formed in the cast pass
+                                     (300, 400, 256, 48),     # ... by the split-K launch
                                      (70, 2304, 128, 64),
-                                     (40, 256, 128, 160)])    # ... by the split-K launch
+                                     (40, 256, 128, 160)])
 def test_forward_exact_integer_case_is_bit_exact(T, n, m, r):
     """Small-integer code values, power-of-two scales: every product and partial sum is exact in
     fp32, so the fp32 output must equal the oracle bit for bit (catches any wrong operand index)."""
