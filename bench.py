@@ -212,6 +212,33 @@ def run_stack(fq, cfg, args):
     print(json.dumps(out))
 
 
+def rank_sweep(fq, cfg, args):
+    """Context table: fwd+bwd time of the melded layer, of the separate-path FP8 LoRA layer and of
+    the bf16 LoRA layer at the headline shape for every adapter rank the library takes (the
+    paper's preliminary analysis and its rank-efficiency table compare FP8 and FP16 adapters over
+    ranks on its own hardware).  Prints one JSON line."""
+    d = workloads.config_layer_inputs(cfg.cfg, 0)
+    m, n, T = d["shape"].m, d["shape"].n, cfg.T
+    x, dy, w = d["x"].cuda(), d["dy"].cuda(), d["w"].cuda()
+    it = max(10, args.steps)
+    rows = []
+    for r in (16, 32, 64, 128, 256):
+        a = (torch.randn(r, n, generator=torch.Generator().manual_seed(r)) / r).cuda()
+        layer = fq.MeldedLinear(T, n, m, r, cfg.k, out_dtype=torch.bfloat16)
+        layer.init_weights(w, a)
+        for _ in range(3):
+            layer.forward(x); layer.backward(dy, lr=cfg.lr)
+        ms_melded = _time_region(lambda: (layer.forward(x), layer.backward(dy, lr=cfg.lr)), it)
+        ms_sep = separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, it)
+        ms_bf16 = bf16_lora_layer(T, n, m, r, it)
+        rows.append({"r": r, "melded_fwd_bwd_ms": ms_melded, "separate_path_fp8_ms": ms_sep, "bf16_lora_ms": ms_bf16,
+                     "melded_vs_separate_fp8": ms_sep / ms_melded, "melded_vs_bf16": ms_bf16 / ms_melded,
+                     "separate_fp8_vs_bf16": ms_bf16 / ms_sep})
+        del layer
+    print(json.dumps({"rank_sweep": rows, "workload": f"T={T}, n={n}, m={m} (config {cfg.cfg} shape), fwd+bwd per layer",
+                      "data": "synthetic"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -222,6 +249,8 @@ def main():
     ap.add_argument("--no-context", action="store_true",
                     help="skip the bf16 LoRA and separate-path FP8 LoRA comparison layers (profiling runs: their "
                          "launches of the same GEMM kernel at other sizes would blur its per-kernel statistics)")
+    ap.add_argument("--rank-sweep", action="store_true",
+                    help="print the rank-sweep context table instead of the benchmark line")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--cpu-reps", type=int, default=4)
     args = ap.parse_args()
@@ -235,6 +264,9 @@ def main():
     import paper_2510_24061_amd as fq
 
     cfg = workloads.CONFIGS[args.config]
+    if args.rank_sweep:
+        rank_sweep(fq, cfg, args)
+        return
     if sum(s.count for s in cfg.layers) > 1:
         run_stack(fq, cfg, args)
         return
