@@ -131,28 +131,34 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
     g.sa = s_x; g.sb = s_w;
     g.c0 = y; g.ldc0 = m; g.c0_is_f32 = (yt == FALQON_F32); g.n_split = m;
     g.c1 = o_a; g.ldc1 = r; g.amax1 = reinterpret_cast<uint32_t*>(amax_oa);
-    e = launch_gemm(g, st);
-    if (e != hipSuccess) return FALQON_ERR_HIP;
-    if (!merged) {
-        // O_A <- x~ A~^T / (s_w s_x): same kernel, K split over workgroups, fp32 partials, then one
-        // pass that adds them in order, rounds to bf16 and takes the maximum
-        const int splits = oa_splits(T, r);
-        int64_t kps = (n + splits - 1) / splits;
-        kps = (kps + 127) / 128 * 128;
-        float* part = reinterpret_cast<float*>(w8 + L.oa_partials);
-        GemmArgs h;
-        h.a = xq; h.lda = n; h.a_fmt = 0;
-        h.b = wq + m * n; h.ldb = n; h.b_is_kn = 0;
-        h.M = T; h.N = r; h.K = n;
-        h.sa = s_x; h.sb = s_w;
-        h.c0 = part; h.ldc0 = r; h.c0_is_f32 = 1; h.n_split = r;
-        h.c1 = nullptr; h.ldc1 = 0; h.amax1 = nullptr;
-        h.splits = splits; h.k_per_split = kps;
-        e = launch_gemm(h, st);
-        if (e != hipSuccess) return FALQON_ERR_HIP;
-        e = launch_sum_partials_bf16(part, splits, T * r, static_cast<uint16_t*>(o_a),
-                                     reinterpret_cast<uint32_t*>(amax_oa), st);
+    if (merged) {
+        e = launch_gemm(g, st);
+        return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
     }
+    // O_A <- x~ A~^T / (s_w s_x): same kernel, K split over workgroups, fp32 partials, then one
+    // pass that adds them in order, rounds to bf16 and takes the maximum.  Nothing orders the two
+    // products, so when the backbone product runs on the large tiles both go out as one launch.
+    const int splits = oa_splits(T, r);
+    int64_t kps = (n + splits - 1) / splits;
+    kps = (kps + 127) / 128 * 128;
+    float* part = reinterpret_cast<float*>(w8 + L.oa_partials);
+    GemmArgs h;
+    h.a = xq; h.lda = n; h.a_fmt = 0;
+    h.b = wq + m * n; h.ldb = n; h.b_is_kn = 0;
+    h.M = T; h.N = r; h.K = n;
+    h.sa = s_x; h.sb = s_w;
+    h.c0 = part; h.ldc0 = r; h.c0_is_f32 = 1; h.n_split = r;
+    h.c1 = nullptr; h.ldc1 = 0; h.amax1 = nullptr;
+    h.splits = splits; h.k_per_split = kps;
+    if (gemm_fwd_pair_supported(g, h)) {
+        e = launch_gemm_fwd_pair(g, h, st);
+    } else {
+        e = launch_gemm(g, st);
+        if (e == hipSuccess) e = launch_gemm(h, st);
+    }
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+    e = launch_sum_partials_bf16(part, splits, T * r, static_cast<uint16_t*>(o_a),
+                                 reinterpret_cast<uint32_t*>(amax_oa), st);
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 

@@ -50,6 +50,10 @@ struct GemmArgs {
 };
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream);
 int64_t gemm_tile_n(int64_t M, int64_t N);   // width of the output tiles launch_gemm picks for an M x N product
+// g (large product, 256x256 tiles) and h (a split-K product on 128x128 tiles) in one launch; both
+// [N,K], E4M3.  Results are those of launch_gemm(g) and launch_gemm(h).
+bool gemm_fwd_pair_supported(const GemmArgs& g, const GemmArgs& h);
+hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_t stream);
 
 // ---- O_A from split-K partials (partials.hip) ---------------------------------------------------
 // out[count] (bf16) = sum over splits of partial[split][count]; folds max|out| into *amax.

@@ -82,21 +82,26 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));
 }
 
+// LDS of one workgroup: operand rings, the left operand three stages deep, the right operand two
+// (160 KB at 256x256).
+template <int WM, int WN, int MB, int NB>
+constexpr int gemm_lds_bytes() { return (3 * WM * MB + 2 * WN * NB) * 32 * BK; }
+
+// One output tile.  `bid` is the workgroup's index in a grid of 8 * chunk workgroups whose index
+// modulo 8 is the XCD it runs on, `split` its K split; `lds` is gemm_lds_bytes() of LDS, 1 KB aligned.
 template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT>
-__global__ void __launch_bounds__(64 * WM * WN)
-gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk)
+__device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, const int tiles_n, const int chunk,
+                                          const int bid, const int split, uint8_t* const lds)
 {
     constexpr int BM = WM * MB * 32, BN = WN * NB * 32, NW = WM * WN;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
     static_assert((BM / 8) % NW == 0 && (B_BYTES / 1024) % NW == 0, "loads must split evenly over waves");
-    // Operand rings: the left operand three stages deep, the right operand two (160 KB at 256x256).
-    __shared__ __attribute__((aligned(1024))) uint8_t lds[3 * A_BYTES + 2 * B_BYTES];
     uint8_t* const lds_b = lds + 3 * A_BYTES;
 
     // ---- workgroup -> tile (XCD aware) ----------------------------------------------------
     // Hardware places workgroup b on XCD b % 8.  XCD x takes tiles [x*chunk, (x+1)*chunk) of a
     // raster that walks panels of 4 tile-rows, tile-column by tile-column.
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int xcd = bid & 7, slot = bid >> 3;
     const int tile_id = xcd * chunk + slot;
     if (slot >= chunk || tile_id >= tiles_m * tiles_n) return;
     constexpr int PH = 4;
@@ -110,14 +115,14 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     const int wm = wave / WN, wn = wave % WN;
     const int64_t m0 = static_cast<int64_t>(tile_m) * BM, n0 = static_cast<int64_t>(tile_n) * BN;
     const int64_t M = g.M, N = g.N;
-    // Split K: workgroup row blockIdx.y multiplies the K range [kbeg, kbeg + K) only and writes
+    // Split K: split `split` multiplies the K range [kbeg, kbeg + K) only and writes
     // its own copy of the output (fp32 partials, summed by a later pass).
-    const int64_t kbeg = static_cast<int64_t>(blockIdx.y) * g.k_per_split;
+    const int64_t kbeg = static_cast<int64_t>(split) * g.k_per_split;
     const int64_t K = (g.K - kbeg) < g.k_per_split ? (g.K - kbeg > 0 ? g.K - kbeg : 0) : g.k_per_split;
     const uint8_t* const ga = g.a + kbeg;
     const uint8_t* const gb = B_KN ? g.b + kbeg * g.ldb : g.b + kbeg;
     uint8_t* const c0p = static_cast<uint8_t*>(g.c0) +
-                         static_cast<int64_t>(blockIdx.y) * M * g.ldc0 * (g.c0_is_f32 ? 4 : 2);
+                         static_cast<int64_t>(split) * M * g.ldc0 * (g.c0_is_f32 ? 4 : 2);
 
     // ---- global -> LDS ----------------------------------------------------------------------
     // Fast path (every K-step that lies fully inside K): address = uniform base + 32-bit lane
@@ -463,6 +468,34 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     }
 }
 
+template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT>
+__global__ void __launch_bounds__(64 * WM * WN)
+gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<WM, WN, MB, NB>()];
+    gemm_tile<WM, WN, MB, NB, B_KN, A_FMT>(g, tiles_m, tiles_n, chunk, blockIdx.x, blockIdx.y, lds);
+}
+
+// Forward product and the adapter's split-K product in one launch.  Both read only x~ and the
+// concatenated weight, so nothing orders them; as two launches the second costs a dispatch, a
+// ramp-up and a drain of its own (about 4 us on this chip) on top of its few microseconds of work.
+// The first n_side workgroups take the adapter tiles (128x128, K split), the rest the backbone
+// tiles (256x256); n_side is a multiple of 8, so workgroup index modulo 8 is still the XCD.
+__global__ void __launch_bounds__(256)
+gemm_fwd_pair_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk,
+                     const GemmArgs h, const int h_tiles_m, const int h_tiles_n, const int h_chunk, const int n_side)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
+    static_assert(gemm_lds_bytes<2, 2, 2, 2>() <= gemm_lds_bytes<2, 2, 4, 4>(), "the small tile fits in the large tile's LDS");
+    const int b = blockIdx.x;
+    if (b < n_side) {
+        const int per_split = 8 * h_chunk;
+        gemm_tile<2, 2, 2, 2, false, 0>(h, h_tiles_m, h_tiles_n, h_chunk, b % per_split, b / per_split, lds);
+    } else {
+        gemm_tile<2, 2, 4, 4, false, 0>(g, tiles_m, tiles_n, chunk, b - n_side, 0, lds);
+    }
+}
+
 template <int WM, int WN, int MB, int NB>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream)
 {
@@ -491,6 +524,23 @@ static bool use_big_tiles(int64_t M, int64_t N)
 }
 
 int64_t gemm_tile_n(int64_t M, int64_t N) { return use_big_tiles(M, N) ? 256 : 128; }
+
+bool gemm_fwd_pair_supported(const GemmArgs& g, const GemmArgs& h)
+{
+    return use_big_tiles(g.M, g.N) && g.splits == 1 && !g.b_is_kn && !h.b_is_kn && g.a_fmt == 0 && h.a_fmt == 0;
+}
+
+hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_t stream)
+{
+    const int tiles_m = static_cast<int>((g.M + 255) / 256), tiles_n = static_cast<int>((g.N + 255) / 256);
+    const int chunk = (tiles_m * tiles_n + 7) / 8;
+    const int h_tiles_m = static_cast<int>((h.M + 127) / 128), h_tiles_n = static_cast<int>((h.N + 127) / 128);
+    const int h_chunk = (h_tiles_m * h_tiles_n + 7) / 8;
+    const int n_side = 8 * h_chunk * h.splits;
+    gemm_fwd_pair_kernel<<<dim3(static_cast<unsigned>(n_side + 8 * chunk)), dim3(256), 0, stream>>>(
+        g, tiles_m, tiles_n, chunk, h, h_tiles_m, h_tiles_n, h_chunk, n_side);
+    return hipGetLastError();
+}
 
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream)
 {
