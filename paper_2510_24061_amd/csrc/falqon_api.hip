@@ -197,12 +197,18 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
     g.sa = s_dy; g.sb = s_w;
     g.c0 = dx; g.ldc0 = n; g.c0_is_f32 = (dxt == FALQON_F32); g.n_split = n;
     g.c1 = nullptr; g.ldc1 = 0; g.amax1 = nullptr;
-    e = launch_gemm(g, st);
+    // dB <- dy~^T O_A~ / (s_dy s_oa);  DeltaBuffer += -lr dB.  Its partial pass reads only dy~ and
+    // O_A, so nothing orders it against the dX product: on the large tiles both go out as one launch.
+    const DbArgs d = make_db_args(dyq, o_a, amax_oa, T, m, r, reinterpret_cast<float*>(w8 + L.db_partials),
+                                  db_splits(T, m));
+    if (gemm_dx_db_pair_supported(g)) {
+        e = launch_gemm_dx_db_pair(g, d, st);
+    } else {
+        e = launch_gemm(g, st);
+        if (e == hipSuccess) e = launch_db_partial(d, st);
+    }
     if (e != hipSuccess) return FALQON_ERR_HIP;
-
-    // dB <- dy~^T O_A~ / (s_dy s_oa);  DeltaBuffer += -lr dB
-    e = launch_db(dyq, s_dy, o_a, amax_oa, T, m, r, d_b, delta_buf, lr,
-                  reinterpret_cast<float*>(w8 + L.db_partials), db_splits(T, m), st);
+    e = launch_db_reduce(d, s_dy, d_b, delta_buf, lr, st);
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 

@@ -61,10 +61,24 @@ hipError_t launch_sum_partials_bf16(const float* partial, int splits, int64_t co
                                     hipStream_t stream);
 int oa_splits(int64_t T, int64_t r);
 
-// ---- adapter gradient (db.hip) -------------------------------------------------------------
-hipError_t launch_db(const uint8_t* dyq, const float* s_dy, const void* o_a, const float* amax_oa,
-                     int64_t T, int64_t m, int64_t r, float* d_b, float* delta_buf, float lr,
-                     float* partials, int splits, hipStream_t stream);
+// ---- adapter gradient (db.hip, db_tile.h) ------------------------------------------------------
+// Two passes: fp32 partials per token split, then their ordered sum with the rescale and the
+// optional proxy-buffer step.
+struct DbArgs {
+    const uint8_t* dyq; const uint16_t* o_a; const float* amax_oa;
+    int64_t T, m, r, tokens_per_split;
+    float* partial;                                                    // [splits][m][r]
+    int i_tiles, splits, p_tiles;                                      // grid of the partial pass
+};
+DbArgs make_db_args(const uint8_t* dyq, const void* o_a, const float* amax_oa, int64_t T, int64_t m, int64_t r,
+                    float* partials, int splits);
+hipError_t launch_db_partial(const DbArgs& d, hipStream_t stream);
+hipError_t launch_db_reduce(const DbArgs& d, const float* s_dy, float* d_b, float* delta_buf, float lr,
+                            hipStream_t stream);
+// Input-gradient GEMM g ([K,N] right operand, E5M2 left operand, 256x256 tiles) and the partial pass
+// of the adapter gradient in one launch: both read only dy~ (and O_A, the weight).
+bool gemm_dx_db_pair_supported(const GemmArgs& g);
+hipError_t launch_gemm_dx_db_pair(const GemmArgs& g, const DbArgs& d, hipStream_t stream);
 
 // ---- proxy update (proxy.hip) ----------------------------------------------------------------
 hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,

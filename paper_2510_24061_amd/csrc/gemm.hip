@@ -27,6 +27,7 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include "db_tile.h"
 #include "falqon_internal.h"
 
 namespace falqon {
@@ -496,6 +497,26 @@ gemm_fwd_pair_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, con
     }
 }
 
+// Input-gradient product and the partial pass of the adapter gradient in one launch, for the same
+// reason: the first n_side workgroups take the adapter-gradient tiles, the rest the 256x256 tiles
+// of dX = dy~ W~.
+__global__ void __launch_bounds__(256)
+gemm_dx_db_pair_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk,
+                       const DbArgs d, const int n_side)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
+    static_assert(dbt::kDbLdsBytes <= static_cast<size_t>(gemm_lds_bytes<2, 2, 4, 4>()), "the dB tiles fit in the GEMM's LDS");
+    static_assert(dbt::kThreads == 256, "one workgroup shape for both kinds of tile");
+    const int b = blockIdx.x;
+    if (b < n_side) {
+        if (b >= d.i_tiles * d.splits * d.p_tiles) return;               // padding up to a multiple of 8
+        const int bi = b % d.i_tiles, rest = b / d.i_tiles;
+        dbt::db_partial_tile(d, bi, rest % d.splits, rest / d.splits, lds, g_zero16);
+    } else {
+        gemm_tile<2, 2, 4, 4, true, 1>(g, tiles_m, tiles_n, chunk, b - n_side, 0, lds);
+    }
+}
+
 template <int WM, int WN, int MB, int NB>
 hipError_t launch_cfg(const GemmArgs& g, hipStream_t stream)
 {
@@ -539,6 +560,21 @@ hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_
     const int n_side = 8 * h_chunk * h.splits;
     gemm_fwd_pair_kernel<<<dim3(static_cast<unsigned>(n_side + 8 * chunk)), dim3(256), 0, stream>>>(
         g, tiles_m, tiles_n, chunk, h, h_tiles_m, h_tiles_n, h_chunk, n_side);
+    return hipGetLastError();
+}
+
+bool gemm_dx_db_pair_supported(const GemmArgs& g)
+{
+    return use_big_tiles(g.M, g.N) && g.splits == 1 && g.b_is_kn && g.a_fmt == 1;
+}
+
+hipError_t launch_gemm_dx_db_pair(const GemmArgs& g, const DbArgs& d, hipStream_t stream)
+{
+    const int tiles_m = static_cast<int>((g.M + 255) / 256), tiles_n = static_cast<int>((g.N + 255) / 256);
+    const int chunk = (tiles_m * tiles_n + 7) / 8;
+    const int n_side = (d.i_tiles * d.splits * d.p_tiles + 7) / 8 * 8;
+    gemm_dx_db_pair_kernel<<<dim3(static_cast<unsigned>(n_side + 8 * chunk)), dim3(256), 0, stream>>>(
+        g, tiles_m, tiles_n, chunk, d, n_side);
     return hipGetLastError();
 }
 
