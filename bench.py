@@ -27,7 +27,7 @@ FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the forward GEMM kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs of this command (profiles/bench_config2_pmc_hbm_traffic_and_mfma.md).
-GEMM_FWD_TRAFFIC_BYTES = 137.2e6   # 101.8 MB fetched (FETCH_SIZE x 1.998) + 35.4 MB written
+GEMM_FWD_TRAFFIC_BYTES = 143.3e6   # 105.3 MB fetched (FETCH_SIZE x 1.998) + 38.0 MB written
 
 
 def _time_region(fn, iters):
@@ -325,6 +325,8 @@ def main():
     tflops_dx = flops_dx / (ms_gemm_dx * 1e-3) / 1e12
     quant_bytes = 3.0 * T * n                      # read bf16 once (second read is cache-served), write FP8
     upd_bytes = 4.0 * m * r + 2.0 * k * n + r * n + 8.0 * k * r   # scores + selected rows in/out + adapter rows + buffer rows
+    # The backbone product launched on its own.  Inside falqon_melded_fwd the same tile code runs in
+    # gemm_fwd_pair_kernel, one launch that also carries the adapter's split-K tiles (see kernels).
     roofline = {"bound": "mfma", "kernel": "gemm_fp8_kernel<2,2,4,4,false,0> (forward, X~ . W~^T, 256 tiles of 256x256)",
                 "achieved": tflops_fwd, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": tflops_fwd / FP8_PEAK_TFLOPS, "traffic": GEMM_FWD_TRAFFIC_BYTES,
@@ -340,6 +342,10 @@ def main():
         "adamw_buffer_step": {"grad_sqnorm_ms": ms_sqnorm, "adamw_delta_ms": ms_adamw,
                               "bytes": 28.0 * m * r, "GB/s": 28.0 * m * r / (ms_adamw * 1e-3) / 1e9,
                               "note": "optional replacement of the SGD buffer step inside melded_bwd; not in the timed step"},
+        "fwd_after_quantize": {"ms_derived": ms_fwd - ms_quant, "flops": 2.0 * T * n * (m + r),
+                               "TFLOP/s": 2.0 * T * n * (m + r) / ((ms_fwd - ms_quant) * 1e-3) / 1e12,
+                               "note": "melded_fwd minus the quantizer: gemm_fwd_pair_kernel (backbone tiles + adapter "
+                                       "split-K tiles in one launch) + the ordered sum of the adapter partials"},
         "calls": {"melded_fwd_ms": ms_fwd, "melded_bwd_ms": ms_bwd, "proxy_update_ms": ms_upd},
         "gemm_flops": {"fwd_backbone": flops_fwd, "fwd_adapter": 2.0 * T * n * r, "dx": flops_dx, "db": flops_db},
     }
