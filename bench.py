@@ -7,6 +7,8 @@ A step is one pass of the whole hot path over one batch of synthetic input: meld
 melded backward (input gradient, adapter gradient, proxy-buffer step) and the row-wise proxy
 update, at the LLaMA-7B attention-projection shape (T = n = m = 4096, r = 64, k = 32).
 All inputs are resident in HBM before the timed region.  One JSON line is printed.
+The defaults (100 warm-up steps, 1000 timed steps, 0.2 s of GPU time) are long enough for the
+clocks to settle: the first few dozen steps after an idle period run about 10 % slower.
 """
 import argparse
 import json
@@ -85,7 +87,7 @@ def bf16_lora_layer(T, n, m, r, iters):
         da = dyb.t() @ x
         return y, dx, db, da
 
-    for _ in range(3):
+    for _ in range(20):
         step()
     return _time_region(step, iters)
 
@@ -102,7 +104,7 @@ def library_fp8_gemm(T, n, m, iters):
     def run():
         return torch._scaled_mm(a, b.t(), scale_a=one, scale_b=one, out_dtype=torch.bfloat16)
 
-    for _ in range(3):
+    for _ in range(20):
         run()
     return _time_region(run, iters)
 
@@ -147,7 +149,7 @@ def separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, iters):
         da = g.t() @ x
         return y, dx, db, da
 
-    for _ in range(3):
+    for _ in range(20):
         step()
     return _time_region(step, iters)
 
@@ -183,8 +185,17 @@ def run_stack(fq, cfg, args):
             for layer in layers:
                 layer.update()
 
-    warm = max(args.warmup, acc) // acc * acc
-    steps = max(args.steps, acc) // acc * acc                      # whole accumulation cycles
+    # whole accumulation cycles; at most about 10 s of timed work and 2 s of warm-up
+    for i in range(acc):
+        train_step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(acc):
+        train_step(i)
+    torch.cuda.synchronize()
+    est = (time.perf_counter() - t0) / acc
+    warm = max(min(args.warmup, int(2.0 / est)), acc) // acc * acc
+    steps = max(min(args.steps, int(10.0 / est)), acc) // acc * acc
     for i in range(warm):
         train_step(i)
     torch.cuda.synchronize()
@@ -242,8 +253,8 @@ def rank_sweep(fq, cfg, args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--config", type=int, default=2, help="workload (2 = the headline LLaMA-7B attention projection; 3-5 run all their layers as a stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
