@@ -405,11 +405,15 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
             uint8_t* srow = lds + (wm * 32 + (lane & 31)) * PITCH;
 #pragma unroll
             for (int ni = 0; ni < NB; ++ni) {
+                // One block at a time leaves the accumulation registers (the empty asm pins the copy
+                // here; left to itself the compiler moves all 256 up front and spills).
+                v16f t = acc[mi][ni];
+                asm volatile("" : "+v"(t));
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int c = wn * NB * 32 + ni * 32 + q * 8 + (lane >> 5) * 4;
-                    const float v0 = acc[mi][ni][4 * q] * inv, v1 = acc[mi][ni][4 * q + 1] * inv;
-                    const float v2 = acc[mi][ni][4 * q + 2] * inv, v3 = acc[mi][ni][4 * q + 3] * inv;
+                    const float v0 = t[4 * q] * inv, v1 = t[4 * q + 1] * inv;
+                    const float v2 = t[4 * q + 2] * inv, v3 = t[4 * q + 3] * inv;
                     if (F32) {
                         *reinterpret_cast<float4*>(srow + c * 4) = make_float4(v0, v1, v2, v3);
                     } else {
