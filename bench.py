@@ -29,7 +29,7 @@ FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch of the forward GEMM kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
 # runs of this command (profiles/bench_config2_pmc_hbm_traffic_and_mfma.md).
-GEMM_FWD_TRAFFIC_BYTES = 143.3e6   # 105.3 MB fetched (FETCH_SIZE x 1.998) + 38.0 MB written
+GEMM_FWD_TRAFFIC_BYTES = 134.7e6   # 101.1 MB fetched (FETCH_SIZE x 1.998) + 33.6 MB written
 
 
 def _time_region(fn, iters):
