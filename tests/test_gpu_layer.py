@@ -288,6 +288,16 @@ def test_full_size_config_sampled(cfg, layer):
     assert np_of(layer_gpu.delta_buf).tobytes() == buf_ref.tobytes()
 
 
+def test_very_tall_input():
+    """300 000 tokens: tens of thousands of tile rows, row offsets far beyond 16 bits."""
+    T, n, m, r, k = 300_000, 256, 256, 16, 8
+    d, wcat, s_w = _inputs(T, n, m, r, outliers=True, seed=4242)
+    print("tall forward", flush=True)
+    _check_forward(T, n, m, r, k, d, wcat, s_w, torch.bfloat16, n_sample=64)
+    print("tall backward", flush=True)
+    _check_backward(T, n, m, r, k, d, wcat, s_w, torch.bfloat16, n_sample=64)
+
+
 def _random_shapes(count, seed):
     """Seeded shapes that mix every tile path: ragged T, n and m not multiples of the K step or
     the tile sizes, all adapter widths, both tile configurations."""

@@ -106,3 +106,30 @@ def test_cast_every_finite_fp32_bit_pattern(fmt):
         bad = np.flatnonzero((got != ref) & fin)
         assert bad.size == 0, (c, xf[bad[:4]], got[bad[:4]], ref[bad[:4]])
         print(f"slice {c} ok", flush=True)
+
+
+def test_quantize_more_than_2_to_31_elements():
+    """Index arithmetic beyond 32 bits: a tensor of 2^31 + 2^16 elements whose largest magnitude is
+    its very last element.  The scale must see it, and codes are compared where 32-bit offsets would
+    wrap: at the start, across the 2^31 boundary and at the end."""
+    cols = 4096
+    rows = (1 << 31) // cols + 16
+    g = torch.Generator().manual_seed(31)
+    block = torch.randn(4096, cols, generator=g).to(torch.bfloat16)
+    x = block.repeat(rows // 4096 + 1, 1)[:rows].contiguous()
+    x[-1, -1] = 1000.0
+    x[(1 << 31) // cols, 5] = -700.0
+    xg = x.cuda()
+    q = torch.empty(rows, cols, dtype=torch.uint8, device="cuda")
+    s = torch.zeros(1, device="cuda")
+    amax = torch.zeros(1, device="cuda")
+    ws = torch.empty(8192, dtype=torch.uint8, device="cuda")
+    fq.quantize(xg, fq.E4M3, q, s, ws, amax_out=amax)
+    torch.cuda.synchronize()
+    assert amax.item() == 1000.0
+    _, s_ref, _ = oracle.quantize(np.full((1, 16), 1000.0, np.float32), oracle.E4M3)
+    assert np.float32(s.item()).tobytes() == s_ref.tobytes()
+    boundary = (1 << 31) // cols
+    for lo, hi in ((0, 256), (boundary - 128, boundary + 128), (rows - 256, rows)):
+        ref, _, _ = oracle.quantize(x[lo:hi].float().numpy(), oracle.E4M3, scale_in=s_ref)
+        assert np.array_equal(np_of(q[lo:hi]), ref), (lo, hi)
