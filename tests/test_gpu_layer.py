@@ -32,6 +32,8 @@ SHAPES = [
     (50, 2176, 256, 64, 8, False),        # K = 17 steps of 128
     (33, 640, 128, 32, 4, False),
     (40, 384, 128, 96, 4, False),
+    # large enough for the paired product launches (256x256 tiles + adapter tiles in one grid), ragged, K tail
+    (2400, 3408, 3328, 32, 9, True),
 ]
 
 
