@@ -250,6 +250,52 @@ def rank_sweep(fq, cfg, args):
                       "data": "synthetic"}))
 
 
+def decoder_block(fq, args):
+    """Context: one LLaMA-13B-shaped decoder block (d = 5120, 40 heads, MLP 13824, 8 x 1024 tokens)
+    forward + backward with real data dependence between its seven projections: melded layers
+    against bf16 LoRA layers (frozen W, trainable A and B) in the same block.  Prints one JSON line."""
+    from paper_2510_24061_amd.nn import LlamaBlock, MeldedLoRALinear
+    d_model, heads, d_mlp, r, k, batch, seq = 5120, 40, 13824, 64, 64, 8, 1024
+    g = torch.Generator(device="cuda").manual_seed(13)
+
+    def melded(i, o):
+        lin = MeldedLoRALinear(i, o, r, k, sgd_lr=2e-4)
+        lin.load_weights(torch.randn(o, i, device="cuda", generator=g) * 0.02,
+                         torch.randn(r, i, device="cuda", generator=g) / r)
+        return lin
+
+    class LoRALinear(torch.nn.Module):
+        def __init__(self, i, o):
+            super().__init__()
+            self.w = torch.nn.Parameter((torch.randn(o, i, device="cuda", generator=g) * 0.02).to(torch.bfloat16),
+                                        requires_grad=False)
+            self.a = torch.nn.Parameter((torch.randn(r, i, device="cuda", generator=g) / r).to(torch.bfloat16))
+            self.b = torch.nn.Parameter(torch.zeros(o, r, device="cuda", dtype=torch.bfloat16))
+
+        def forward(self, x):
+            return x @ self.w.t() + (x @ self.a.t()) @ self.b.t()
+
+    x = torch.randn(batch, seq, d_model, device="cuda", generator=g).to(torch.bfloat16)
+    out = {}
+    for name, make in (("melded_fp8", melded), ("bf16_lora", LoRALinear)):
+        block = LlamaBlock(d_model, heads, d_mlp, make)
+        xin = x.clone().requires_grad_(True)
+
+        def step():
+            y = block(xin)
+            y.backward(y.detach())                          # any gradient of the right shape
+
+        for _ in range(5):
+            step()
+        out[name + "_ms"] = _time_region(step, max(10, min(args.steps, 50)))
+        del block
+    out["speedup"] = out["bf16_lora_ms"] / out["melded_fp8_ms"]
+    out["backbone_gemm_flops"] = 2 * 2.0 * batch * seq * (4 * d_model * d_model + 3 * d_model * d_mlp)   # fwd + dX
+    out["workload"] = (f"decoder block d={d_model}, heads={heads}, mlp={d_mlp}, tokens={batch}x{seq}, r={r}: "
+                       "fwd+bwd, PyTorch RMSNorm / causal attention / SwiGLU between the projections")
+    print(json.dumps({"decoder_block": out, "data": "synthetic"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -260,6 +306,8 @@ def main():
     ap.add_argument("--no-context", action="store_true",
                     help="skip the bf16 LoRA and separate-path FP8 LoRA comparison layers (profiling runs: their "
                          "launches of the same GEMM kernel at other sizes would blur its per-kernel statistics)")
+    ap.add_argument("--decoder-block", action="store_true",
+                    help="print the decoder-block context measurement instead of the benchmark line")
     ap.add_argument("--rank-sweep", action="store_true",
                     help="print the rank-sweep context table instead of the benchmark line")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
@@ -277,6 +325,9 @@ def main():
     cfg = workloads.CONFIGS[args.config]
     if args.rank_sweep:
         rank_sweep(fq, cfg, args)
+        return
+    if args.decoder_block:
+        decoder_block(fq, args)
         return
     if sum(s.count for s in cfg.layers) > 1:
         run_stack(fq, cfg, args)

@@ -1,0 +1,153 @@
+"""The melded layer as a PyTorch module: autograd plumbing around the C-ABI calls.
+
+Nothing is computed here.  `MeldedLoRALinear.forward` calls `falqon_melded_fwd`, its autograd
+backward calls `falqon_melded_bwd` (which also takes the buffer step when `lr` is set), and
+`proxy_update()` / `adamw_step()` call the update entry points.  The module owns the layer's
+persistent state (concatenated FP8 weight, its scale, the proxy buffer) and a workspace; per-call
+outputs are fresh tensors so that a layer may be used several times before its backward runs.
+"""
+from typing import Optional
+
+import torch
+
+from . import binding as _b
+
+
+class _MeldedFn(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x: torch.Tensor, layer: "MeldedLoRALinear") -> torch.Tensor:
+        lead = x.shape[:-1]
+        x2 = x.reshape(-1, layer.in_features)
+        if x2.dtype != torch.bfloat16:
+            x2 = x2.to(torch.bfloat16)
+        x2 = x2.contiguous()
+        T = x2.shape[0]
+        dev = x2.device
+        ws = layer._workspace(T)
+        xq = torch.empty(T, layer.in_features, dtype=torch.uint8, device=dev)
+        s_x = torch.empty(1, dtype=torch.float32, device=dev)
+        y = torch.empty(T, layer.out_features, dtype=torch.bfloat16, device=dev)
+        o_a = torch.empty(T, layer.rank, dtype=torch.bfloat16, device=dev)
+        amax_oa = torch.empty(1, dtype=torch.float32, device=dev)
+        _b.melded_fwd(x2, layer.wq, layer.s_w, layer.out_features, layer.rank, xq, s_x, y, o_a, amax_oa, ws)
+        ctx.layer, ctx.T, ctx.lead = layer, T, lead
+        ctx.save_for_backward(o_a, amax_oa)
+        return y.reshape(*lead, layer.out_features)
+
+    @staticmethod
+    def backward(ctx, dy: torch.Tensor):
+        layer, T = ctx.layer, ctx.T
+        o_a, amax_oa = ctx.saved_tensors
+        dy2 = dy.reshape(T, layer.out_features)
+        if dy2.dtype != torch.bfloat16:
+            dy2 = dy2.to(torch.bfloat16)
+        dy2 = dy2.contiguous()
+        dev = dy2.device
+        dyq = torch.empty(T, layer.out_features, dtype=torch.uint8, device=dev)
+        s_dy = torch.empty(1, dtype=torch.float32, device=dev)
+        dx = torch.empty(T, layer.in_features, dtype=torch.bfloat16, device=dev)
+        # with an SGD rate the buffer step happens inside the call; otherwise d_b waits for adamw_step()
+        buf = layer.delta_buf if layer.sgd_lr is not None else None
+        _b.melded_bwd(dy2, layer.wq, layer.s_w, o_a, amax_oa, layer.in_features, layer.rank, dyq, s_dy, dx,
+                      layer.d_b, buf, layer.sgd_lr if layer.sgd_lr is not None else 0.0, layer._workspace(T))
+        return dx.reshape(*ctx.lead, layer.in_features), None
+
+
+class MeldedLoRALinear(torch.nn.Module):
+    """y = x W'^T with W' the FP8 backbone that already contains the adapter; trainable only through
+    the proxy buffer.  `sgd_lr` set: backward applies `DeltaBuffer += -lr dB` itself.  `sgd_lr=None`:
+    backward leaves dB in `d_b`; call `adamw_step()` (after `grad_sqnorm()` over all layers if the
+    gradient norm is clipped), then `proxy_update()` at the chosen cadence."""
+
+    def __init__(self, in_features: int, out_features: int, rank: int, top_k: int, sgd_lr: Optional[float] = 2e-4,
+                 device="cuda"):
+        super().__init__()
+        self.in_features, self.out_features, self.rank, self.top_k = in_features, out_features, rank, top_k
+        self.sgd_lr = sgd_lr
+        dev = torch.device(device)
+        self.register_buffer("wq", torch.zeros(out_features + rank, in_features, dtype=torch.uint8, device=dev))
+        self.register_buffer("s_w", torch.ones(1, dtype=torch.float32, device=dev))
+        self.register_buffer("delta_buf", torch.zeros(out_features, rank, dtype=torch.float32, device=dev))
+        self.d_b = torch.zeros(out_features, rank, dtype=torch.float32, device=dev)
+        self.idx = torch.zeros(top_k, dtype=torch.int32, device=dev)
+        self.exp_avg = None
+        self.exp_avg_sq = None
+        self._ws = None
+        self._ws_tokens = 0
+
+    def _workspace(self, T: int) -> torch.Tensor:
+        if self._ws is None or T > self._ws_tokens:
+            nbytes = _b.workspace_bytes(T, self.in_features, self.out_features, self.rank)
+            if nbytes == 0:
+                raise ValueError("invalid layer shape")
+            self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.wq.device)
+            self._ws_tokens = T
+        return self._ws
+
+    @torch.no_grad()
+    def load_weights(self, w: torch.Tensor, a: torch.Tensor) -> None:
+        """W~, s_w <- Q(W); A~ <- cast(A * s_w); buffer <- 0 (the initialization steps after the SVD)."""
+        ws = self._workspace(16)
+        s_tmp = torch.zeros(1, dtype=torch.float32, device=self.wq.device)
+        _b.quantize(w.float().contiguous(), _b.E4M3, self.wq[: self.out_features], self.s_w, ws)
+        _b.quantize(a.float().contiguous(), _b.E4M3, self.wq[self.out_features:], s_tmp, ws, scale_in=self.s_w)
+        self.delta_buf.zero_()
+
+    def forward(self, x: torch.Tensor) -> torch.Tensor:
+        return _MeldedFn.apply(x, self)
+
+    @torch.no_grad()
+    def grad_sqnorm(self, sum_sq: torch.Tensor) -> None:
+        _b.grad_sqnorm(self.d_b, sum_sq, self._workspace(16))
+
+    @torch.no_grad()
+    def adamw_step(self, step: int, sum_sq: Optional[torch.Tensor] = None, lr: float = 2e-4, beta1: float = 0.9,
+                   beta2: float = 0.999, eps: float = 1e-8, max_norm: float = 0.3) -> None:
+        if self.exp_avg is None:
+            self.exp_avg = torch.zeros_like(self.d_b)
+            self.exp_avg_sq = torch.zeros_like(self.d_b)
+        _b.adamw_delta(self.d_b, self.exp_avg, self.exp_avg_sq, self.delta_buf, step, lr, beta1, beta2, eps, sum_sq,
+                       max_norm)
+
+    @torch.no_grad()
+    def proxy_update(self, clear_selected: bool = True) -> torch.Tensor:
+        _b.proxy_update(self.delta_buf, self.wq, self.out_features, self.rank, self.top_k, self.idx,
+                        self._workspace(16), clear_selected)
+        return self.idx
+
+
+class _RMSNorm(torch.nn.Module):
+    def __init__(self, d: int, device="cuda"):
+        super().__init__()
+        self.weight = torch.nn.Parameter(torch.ones(d, dtype=torch.bfloat16, device=device), requires_grad=False)
+
+    def forward(self, x):
+        v = x.float()
+        return (v * torch.rsqrt(v.pow(2).mean(-1, keepdim=True) + 1e-5)).to(x.dtype) * self.weight
+
+
+class LlamaBlock(torch.nn.Module):
+    """One LLaMA decoder block whose seven projections are melded layers (q, k, v, o, gate, up,
+    down); normalisation, attention and the SwiGLU product are plain PyTorch operations, there only
+    to put real data dependence between the projections.  `linear(in, out)` builds a projection, so
+    the same block can be instantiated with another linear layer for comparison."""
+
+    def __init__(self, d_model: int, n_heads: int, d_mlp: int, linear, device="cuda"):
+        super().__init__()
+        self.n_heads = n_heads
+        self.norm1, self.norm2 = _RMSNorm(d_model, device), _RMSNorm(d_model, device)
+        self.q, self.k, self.v, self.o = (linear(d_model, d_model) for _ in range(4))
+        self.gate, self.up = linear(d_model, d_mlp), linear(d_model, d_mlp)
+        self.down = linear(d_mlp, d_model)
+
+    def forward(self, x):                                              # x: [batch, seq, d_model] bf16
+        B, S, D = x.shape
+        h = self.norm1(x)
+        q, k, v = (p(h).reshape(B, S, self.n_heads, D // self.n_heads).transpose(1, 2) for p in (self.q, self.k, self.v))
+        a = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
+        x = x + self.o(a.transpose(1, 2).reshape(B, S, D))
+        h = self.norm2(x)
+        return x + self.down(torch.nn.functional.silu(self.gate(h)) * self.up(h))
+
+    def projections(self):
+        return [self.q, self.k, self.v, self.o, self.gate, self.up, self.down]
