@@ -93,15 +93,29 @@ topk_rank_kernel(const double* __restrict__ score, int64_t m, int64_t k, int64_t
         // rows below the wave's rows: ties count; rows above: they do not
         const int64_t lo_end = base - c0 < 0 ? 0 : (base - c0 > n_here ? n_here : base - c0);
         const int64_t hi_begin = base + kRankRows - c0 < 0 ? 0 : (base + kRankRows - c0 > n_here ? n_here : base + kRankRows - c0);
-        for (int e = lane; e < lo_end; e += 64) {
-            const uint64_t kj = s_key[e];
+        // eight keys per lane and step, read together (one LDS latency per step instead of eight);
+        // a slot beyond the range reads key 0 of the chunk and is masked out of the count
+        for (int e0 = lane; e0 < lo_end; e0 += 64 * 8) {
+            uint64_t kj[8];
 #pragma unroll
-            for (int q = 0; q < kRankRows; ++q) cnt[q] += kj >= ki[q] ? 1 : 0;
+            for (int u = 0; u < 8; ++u) kj[u] = s_key[e0 + 64 * u < lo_end ? e0 + 64 * u : 0];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool in = e0 + 64 * u < lo_end;
+#pragma unroll
+                for (int q = 0; q < kRankRows; ++q) cnt[q] += (in && kj[u] >= ki[q]) ? 1 : 0;
+            }
         }
-        for (int e = static_cast<int>(hi_begin) + lane; e < n_here; e += 64) {
-            const uint64_t kj = s_key[e];
+        for (int e0 = static_cast<int>(hi_begin) + lane; e0 < n_here; e0 += 64 * 8) {
+            uint64_t kj[8];
 #pragma unroll
-            for (int q = 0; q < kRankRows; ++q) cnt[q] += kj > ki[q] ? 1 : 0;
+            for (int u = 0; u < 8; ++u) kj[u] = s_key[e0 + 64 * u < n_here ? e0 + 64 * u : 0];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const bool in = e0 + 64 * u < n_here;
+#pragma unroll
+                for (int q = 0; q < kRankRows; ++q) cnt[q] += (in && kj[u] > ki[q]) ? 1 : 0;
+            }
         }
         if (lane < kRankRows && base + lane >= c0 && base + lane < c0 + n_here) {       // the wave's own rows
             const uint64_t kj = s_key[base + lane - c0];
