@@ -53,6 +53,7 @@ def lib():
         L.orc_row_scores.argtypes = [p, c.c_int64, c.c_int64, p]
         L.orc_topk_rows.argtypes = [p, c.c_int64, c.c_int64, p]
         L.orc_proxy_update.argtypes = [p, p, c.c_int64, c.c_int64, c.c_int64, c.c_int64, p, c.c_int]
+        L.orc_init_residual.argtypes = [p, p, c.c_float, c.c_int64, p]
         L.orc_num_threads.restype = c.c_int
         _lib = L
     return _lib
@@ -210,6 +211,33 @@ def proxy_update(buf, wq, m: int, r: int, k: int, clear_selected: bool = True):
     idx = np.empty(k, np.int32)
     lib().orc_proxy_update(_ptr(b), _ptr(w), n, m, r, k, _ptr(idx), 1 if clear_selected else 0)
     return idx, w, b
+
+
+def init_residual(w, wq, s_w) -> np.ndarray:
+    """E = DQ(W~) - W in fp32 (initialization algorithm, line 4, with the sign of the reformulation equation)."""
+    wf = _c(w, np.float32)
+    q = _c(wq, np.uint8)
+    assert wf.shape == q.shape
+    e = np.empty(wf.shape, np.float32)
+    lib().orc_init_residual(_ptr(wf), _ptr(q), float(s_w), wf.size, _ptr(e))
+    return e
+
+
+def svd_right_factor(e, r: int):
+    """Rank-r truncated SVD of E (initialization algorithm, line 5) by the library's full SVD in fp64:
+    E ~ B A with B = U_r sqrt(S_r), A = sqrt(S_r) V_r^T.  Returns (A fp64 [r, n], S fp64 [min(m, n)])."""
+    u, sv, vt = np.linalg.svd(np.asarray(e, np.float64), full_matrices=False)
+    return np.sqrt(sv[:r])[:, None] * vt[:r], sv
+
+
+def init_adapter(w, r: int):
+    """Lines 3-6 of the initialization algorithm: W~, s_w <- Q(W); E; A^ <- SVD(E, r); A~ <- cast(A^ s_w).
+    Returns dict(wq, s_w, e, a_hat, a_q, sv)."""
+    wq, s_w, _ = quantize(w, E4M3)
+    e = init_residual(w, wq, s_w)
+    a_hat, sv = svd_right_factor(e, r)
+    a_q, _, _ = quantize(a_hat.astype(np.float32), E4M3, scale_in=s_w)
+    return dict(wq=wq, s_w=s_w, e=e, a_hat=a_hat, a_q=a_q, sv=sv)
 
 
 # --------------------------------------------------------------------------------------

@@ -398,6 +398,22 @@ void orc_proxy_update(float* buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, 
             for (int64_t p = 0; p < r; ++p) buf[(int64_t)idx[a] * r + p] = 0.0f;
 }
 
+/* ------------------------------------------------------------------------- */
+/* Initialization, residual step (initialization algorithm, line 4; the       */
+/* reformulation equation fixes the sign): the quantization error the adapter */
+/* is read out of,                                                            */
+/*   E[i,j] = fl32( fl32( dec(wq[i,j]) / s_w ) - w[i,j] )  =  DQ(W~) - W      */
+/* so that DQ(W~) = W + E and the rank-r part of E plays the role of B A.     */
+/* ------------------------------------------------------------------------- */
+void orc_init_residual(const float* w, const uint8_t* wq, float s_w, int64_t count, float* e)
+{
+    for (int64_t i = 0; i < count; ++i) {
+        volatile float dq = (float)orc_fp8_decode(wq[i], 0) / s_w;
+        volatile float d = dq - w[i];
+        e[i] = d;
+    }
+}
+
 int orc_num_threads(void)
 {
     int nthreads = 1;
