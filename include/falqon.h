@@ -214,6 +214,33 @@ falqon_status falqon_adamw_delta(const float* d_b, float* exp_avg, float* exp_av
                                  int64_t m, int64_t r, int64_t step, double lr, double beta1, double beta2,
                                  double eps, const double* sum_sq, double max_norm, void* stream);
 
+/*
+ * Initialization (the paper's initialization algorithm; once per layer, off the hot path):
+ *
+ *   line 3   W~, s_w <- Q(W)                   falqon_quantize
+ *   line 4   E = DQ(W~) - W                    falqon_init_residual   (the sign the reformulation
+ *                                              equation fixes: DQ(W~) = W + E, E ~ B^ A^)
+ *   line 5   B^, A^ <- SVD(E, r)               falqon_svd_right_factor: A^ = sqrt(S_r) V_r^T; B^ is
+ *                                              never needed (it is implicit in W~)
+ *   line 6   A~ <- cast(A^ * s_w)              falqon_quantize with scale_in = s_w into rows [m, m+r)
+ *
+ * falqon_init_residual: e[i,j] = fl32( fl32(value(wq[i,j]) / s_w) - w[i,j] ), fp32 [m, n].
+ *
+ * falqon_svd_right_factor: randomized subspace iteration with l = r + 8 vectors started from the
+ * caller's Gaussian matrix omega (fp32 [l, n]) and `iters` rounds of multiplication by E^T E, then a
+ * Rayleigh-Ritz step (l x l symmetric eigenproblem in fp64).  a_out (fp32 [r, n]) has orthogonal
+ * rows with squared norms sigma_out[i] (the Ritz values, approximations from below of the r
+ * largest singular values, in descending order); the sign of each row is arbitrary.  The row space
+ * converges to that of the exact truncated SVD at the rate (sigma_{l+1} / sigma_r)^(2 iters + 1).
+ * 16 <= r <= 120, r a multiple of 8; m, n multiples of 4; ws of falqon_svd_workspace_bytes(m, n, r).
+ */
+falqon_status falqon_init_residual(const float* w, const uint8_t* wq, const float* s_w, int64_t m, int64_t n,
+                                   float* e, void* stream);
+size_t falqon_svd_workspace_bytes(int64_t m, int64_t n, int64_t r);
+falqon_status falqon_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega,
+                                      int iters, float* a_out, float* sigma_out,
+                                      void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -61,6 +61,12 @@ def lib():
         L.falqon_adamw_delta.restype = c.c_int
         L.falqon_adamw_delta.argtypes = [f32p, f32p, f32p, f32p, i64, i64, i64, c.c_double, c.c_double, c.c_double,
                                          c.c_double, vp, c.c_double, vp]
+        L.falqon_init_residual.restype = c.c_int
+        L.falqon_init_residual.argtypes = [f32p, vp, f32p, i64, i64, f32p, vp]
+        L.falqon_svd_workspace_bytes.restype = c.c_size_t
+        L.falqon_svd_workspace_bytes.argtypes = [i64, i64, i64]
+        L.falqon_svd_right_factor.restype = c.c_int
+        L.falqon_svd_right_factor.argtypes = [f32p, i64, i64, i64, f32p, c.c_int, f32p, f32p, vp, c.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -163,6 +169,27 @@ def adamw_delta(d_b, exp_avg, exp_avg_sq, delta_buf, step: int, lr: float = 2e-4
     st = lib().falqon_adamw_delta(_p(d_b), _p(exp_avg), _p(exp_avg_sq), _p(delta_buf), m, r, int(step), lr, beta1,
                                   beta2, eps, _p(sum_sq) if sum_sq is not None else None, max_norm, _stream())
     _check(st, "falqon_adamw_delta")
+
+
+def init_residual(w, wq, s_w, e) -> None:
+    """e = DQ(wq) - w (fp32 [m, n])."""
+    _dev(w, wq, s_w, e)
+    m, n = w.shape
+    st = lib().falqon_init_residual(_p(w), _p(wq), _p(s_w), m, n, _p(e), _stream())
+    _check(st, "falqon_init_residual")
+
+
+def svd_workspace_bytes(m: int, n: int, r: int) -> int:
+    return int(lib().falqon_svd_workspace_bytes(m, n, r))
+
+
+def svd_right_factor(e, r: int, omega, iters: int, a_out, sigma_out, ws) -> None:
+    """a_out = sqrt(S_r) V_r^T of e (fp32 [m, n]); omega is a Gaussian fp32 [r + 8, n] start matrix."""
+    _dev(e, omega, a_out, sigma_out, ws)
+    m, n = e.shape
+    st = lib().falqon_svd_right_factor(_p(e), m, n, r, _p(omega), iters, _p(a_out), _p(sigma_out), _p(ws),
+                                       ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_svd_right_factor")
 
 
 class MeldedLinear:

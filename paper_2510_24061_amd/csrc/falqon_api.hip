@@ -289,4 +289,42 @@ falqon_status falqon_adamw_delta(const float* d_b, float* exp_avg, float* exp_av
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 
+static bool bad_svd_shape(int64_t m, int64_t n, int64_t r)
+{
+    return m < 16 || n < 16 || (m % 4) || (n % 4) || r < 16 || r > 120 || (r % 8) || r + 8 > m || r + 8 > n ||
+           m > (int64_t(1) << 20) || n > (int64_t(1) << 20);
+}
+
+falqon_status falqon_init_residual(const float* w, const uint8_t* wq, const float* s_w, int64_t m, int64_t n,
+                                   float* e, void* stream)
+{
+    if (m < 1 || n < 4 || (n % 4) || m > (int64_t(1) << 20) || n > (int64_t(1) << 20)) return FALQON_ERR_SHAPE;
+    if (!w || !wq || !s_w || !e) return FALQON_ERR_NULL;
+    if (misaligned(w) || misaligned(wq) || misaligned(e) || (reinterpret_cast<uintptr_t>(s_w) & 3u))
+        return FALQON_ERR_ALIGN;
+    hipError_t err = launch_init_residual(w, wq, s_w, m * n, e, static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+size_t falqon_svd_workspace_bytes(int64_t m, int64_t n, int64_t r)
+{
+    if (bad_svd_shape(m, n, r)) return 0;
+    return svd_layout(m, n, r).total;
+}
+
+falqon_status falqon_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega,
+                                      int iters, float* a_out, float* sigma_out,
+                                      void* ws, size_t ws_bytes, void* stream)
+{
+    if (bad_svd_shape(m, n, r) || iters < 0 || iters > 64) return FALQON_ERR_SHAPE;
+    if (!e || !omega || !a_out || !sigma_out) return FALQON_ERR_NULL;
+    if (misaligned(e) || misaligned(omega) || misaligned(a_out) || (reinterpret_cast<uintptr_t>(sigma_out) & 3u))
+        return FALQON_ERR_ALIGN;
+    if (!ws || ws_bytes < svd_layout(m, n, r).total) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    hipError_t err = launch_svd_right_factor(e, m, n, r, omega, iters, a_out, sigma_out, static_cast<uint8_t*>(ws),
+                                             static_cast<hipStream_t>(stream));
+    return err == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
 }  // extern "C"

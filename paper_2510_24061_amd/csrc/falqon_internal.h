@@ -85,6 +85,14 @@ hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t
                                int32_t* idx_out, int clear_selected, double* scores, float* delta_sel,
                                hipStream_t stream);
 
+// ---- initialization (init.hip) -----------------------------------------------------------------
+hipError_t launch_init_residual(const float* w, const uint8_t* wq, const float* s_w, int64_t count, float* e,
+                                hipStream_t stream);
+struct SvdLayout { size_t z, y, h, p, lambda, order, total; };   // offsets into the workspace, l = r + 8 vectors
+SvdLayout svd_layout(int64_t m, int64_t n, int64_t r);
+hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega, int iters,
+                                   float* a_out, float* sigma_out, uint8_t* ws, hipStream_t stream);
+
 // ---- optimizer step into the proxy buffer (optimizer.hip) ------------------------------------
 // partials: at least 256 doubles of scratch
 hipError_t launch_grad_sqnorm(const float* g, int64_t count, double* sum_sq, double* partials, hipStream_t stream);

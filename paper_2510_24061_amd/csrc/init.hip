@@ -1,0 +1,384 @@
+// Initialization (the paper's initialization algorithm): the quantization residual
+//   E = DQ(W~) - W            (line 4, with the sign the reformulation equation fixes)
+// and the right factor of its rank-r truncated SVD,  A^ = sqrt(S_r) V_r^T  (line 5), which the
+// caller then casts with the backbone's scale (line 6, falqon_quantize with scale_in).
+//
+// This runs once per layer, before training; it is off the hot path and written for clarity, not
+// for the last microsecond.  The SVD is a randomized subspace iteration (the paper only says "SVD";
+// a truncated factor is all it needs):
+//   Z0 = orth(Omega)                         l = r + 8 rows of length n, Omega Gaussian (caller's)
+//   repeat q times:  Y = orth(Z E^T);  Z = orth(Y E)
+//   Y = Z E^T;  H = Y Y^T (l x l, fp64);  H = P diag(lambda) P^T  (cyclic Jacobi, fp64)
+//   A^[i,:] = lambda_i^(1/4) * sum_c P[c,i] Z[c,:]      for the r largest lambda_i = sigma_i^2
+// Products with E accumulate in fp32, everything l x l and every inner product of the
+// orthonormalisation in fp64.
+#include "falqon_internal.h"
+
+namespace falqon {
+namespace {
+
+constexpr int kThreads = 256;
+
+__global__ void __launch_bounds__(kThreads)
+init_residual_kernel(const float* __restrict__ w, const uint8_t* __restrict__ wq, const float* __restrict__ s_w,
+                     int64_t count, float* __restrict__ e)
+{
+    const float s = *s_w;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * 4;
+    for (int64_t i = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4; i < count; i += stride) {
+        const float4 wv = *reinterpret_cast<const float4*>(w + i);
+        const uint32_t c = *reinterpret_cast<const uint32_t*>(wq + i);
+        float4 o;
+        // IEEE division and subtraction, unfused, as the definition has them
+        o.x = __fsub_rn(__fdiv_rn(__builtin_amdgcn_cvt_f32_fp8(static_cast<int>(c), 0), s), wv.x);
+        o.y = __fsub_rn(__fdiv_rn(__builtin_amdgcn_cvt_f32_fp8(static_cast<int>(c), 1), s), wv.y);
+        o.z = __fsub_rn(__fdiv_rn(__builtin_amdgcn_cvt_f32_fp8(static_cast<int>(c), 2), s), wv.z);
+        o.w = __fsub_rn(__fdiv_rn(__builtin_amdgcn_cvt_f32_fp8(static_cast<int>(c), 3), s), wv.w);
+        *reinterpret_cast<float4*>(e + i) = o;
+    }
+}
+
+__global__ void __launch_bounds__(kThreads)
+copy_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t count)
+{
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride) dst[i] = src[i];
+}
+
+constexpr int kMaxL = 128;                 // vectors in the subspace (r + 8 <= 128)
+constexpr int kPerThread = kMaxL / 4;      // vectors per thread in the two products
+
+// Y[c][i] = sum_j E[i][j] Z[c][j]:  a workgroup owns 64 rows of E and walks j in chunks of 32.
+// thread: row i = t % 64, vectors c = t / 64, t / 64 + 4, ...
+__global__ void __launch_bounds__(kThreads)
+apply_e_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* __restrict__ z, int l,
+               float* __restrict__ y)
+{
+    __shared__ float s_e[64][33];
+    __shared__ float s_z[kMaxL][33];
+    const int ti = threadIdx.x & 63, tg = threadIdx.x >> 6;
+    const int64_t i0 = static_cast<int64_t>(blockIdx.x) * 64;
+    float acc[kPerThread];
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) acc[u] = 0.0f;
+    for (int64_t j0 = 0; j0 < n; j0 += 32) {
+        __syncthreads();
+        for (int q = threadIdx.x; q < 64 * 32; q += kThreads) {
+            const int row = q >> 5, col = q & 31;
+            const int64_t gi = i0 + row, gj = j0 + col;
+            s_e[row][col] = (gi < m && gj < n) ? e[gi * n + gj] : 0.0f;
+        }
+        for (int q = threadIdx.x; q < l * 32; q += kThreads) {
+            const int c = q >> 5, col = q & 31;
+            const int64_t gj = j0 + col;
+            s_z[c][col] = gj < n ? z[static_cast<int64_t>(c) * n + gj] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int jj = 0; jj < 32; ++jj) {
+            const float ev = s_e[ti][jj];
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) {
+                const int c = tg + 4 * u;
+                if (c < l) acc[u] = fmaf(ev, s_z[c][jj], acc[u]);
+            }
+        }
+    }
+    if (i0 + ti < m) {
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int c = tg + 4 * u;
+            if (c < l) y[static_cast<int64_t>(c) * m + i0 + ti] = acc[u];
+        }
+    }
+}
+
+// Z[c][j] = sum_i E[i][j] Y[c][i]:  a workgroup owns 64 columns of E and walks i in chunks of 32.
+__global__ void __launch_bounds__(kThreads)
+apply_et_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* __restrict__ y, int l,
+                float* __restrict__ z)
+{
+    __shared__ float s_e[32][65];
+    __shared__ float s_y[kMaxL][33];
+    const int tj = threadIdx.x & 63, tg = threadIdx.x >> 6;
+    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * 64;
+    float acc[kPerThread];
+#pragma unroll
+    for (int u = 0; u < kPerThread; ++u) acc[u] = 0.0f;
+    for (int64_t i0 = 0; i0 < m; i0 += 32) {
+        __syncthreads();
+        for (int q = threadIdx.x; q < 32 * 64; q += kThreads) {
+            const int row = q >> 6, col = q & 63;
+            const int64_t gi = i0 + row, gj = j0 + col;
+            s_e[row][col] = (gi < m && gj < n) ? e[gi * n + gj] : 0.0f;
+        }
+        for (int q = threadIdx.x; q < l * 32; q += kThreads) {
+            const int c = q >> 5, row = q & 31;
+            const int64_t gi = i0 + row;
+            s_y[c][row] = gi < m ? y[static_cast<int64_t>(c) * m + gi] : 0.0f;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int ii = 0; ii < 32; ++ii) {
+            const float ev = s_e[ii][tj];
+#pragma unroll
+            for (int u = 0; u < kPerThread; ++u) {
+                const int c = tg + 4 * u;
+                if (c < l) acc[u] = fmaf(ev, s_y[c][ii], acc[u]);
+            }
+        }
+    }
+    if (j0 + tj < n) {
+#pragma unroll
+        for (int u = 0; u < kPerThread; ++u) {
+            const int c = tg + 4 * u;
+            if (c < l) z[static_cast<int64_t>(c) * n + j0 + tj] = acc[u];
+        }
+    }
+}
+
+// Orthonormalise the l rows of v[l][len] in place: classical Gram-Schmidt applied twice per row
+// (inner products in fp64), one workgroup of 1024 threads.  A row that vanishes is left as zeros.
+constexpr int kOrthThreads = 1024;
+
+__device__ __forceinline__ double block_sum(double x, double* s_red /* [16] */)
+{
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = x;
+    __syncthreads();
+    double t = 0.0;
+    for (int w = 0; w < kOrthThreads / 64; ++w) t += s_red[w];
+    return t;
+}
+
+__global__ void __launch_bounds__(kOrthThreads)
+orthonormalize_rows_kernel(float* __restrict__ v, int l, int64_t len)
+{
+    __shared__ double s_dot[kMaxL];
+    __shared__ double s_red[kOrthThreads / 64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    for (int c = 0; c < l; ++c) {
+        float* vc = v + static_cast<int64_t>(c) * len;
+        for (int pass = 0; pass < 2; ++pass) {
+            // d_p = <v_c, v_p> for every p < c: wave w takes p = w, w + 16, ...
+            for (int p = wave; p < c; p += kOrthThreads / 64) {
+                const float* vp = v + static_cast<int64_t>(p) * len;
+                double d = 0.0;
+                for (int64_t j = lane; j < len; j += 64) d += static_cast<double>(vc[j]) * static_cast<double>(vp[j]);
+                for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, 64);
+                if (lane == 0) s_dot[p] = d;
+            }
+            __syncthreads();
+            for (int64_t j = threadIdx.x; j < len; j += kOrthThreads) {
+                double x = static_cast<double>(vc[j]);
+                for (int p = 0; p < c; ++p) x -= s_dot[p] * static_cast<double>(v[static_cast<int64_t>(p) * len + j]);
+                vc[j] = static_cast<float>(x);
+            }
+            __syncthreads();
+        }
+        double nn = 0.0;
+        for (int64_t j = threadIdx.x; j < len; j += kOrthThreads) nn += static_cast<double>(vc[j]) * static_cast<double>(vc[j]);
+        nn = block_sum(nn, s_red);
+        const double inv = nn > 0.0 ? 1.0 / sqrt(nn) : 0.0;
+        for (int64_t j = threadIdx.x; j < len; j += kOrthThreads) vc[j] = static_cast<float>(static_cast<double>(vc[j]) * inv);
+        __syncthreads();
+    }
+}
+
+// H[a][b] = sum_i Y[a][i] Y[b][i] in fp64; grid (l, l)
+__global__ void __launch_bounds__(kThreads)
+gram_kernel(const float* __restrict__ y, int l, int64_t m, double* __restrict__ h)
+{
+    __shared__ double s_red[kThreads / 64];
+    const float* ya = y + static_cast<int64_t>(blockIdx.x) * m;
+    const float* yb = y + static_cast<int64_t>(blockIdx.y) * m;
+    double d = 0.0;
+    for (int64_t i = threadIdx.x; i < m; i += kThreads) d += static_cast<double>(ya[i]) * static_cast<double>(yb[i]);
+    for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, 64);
+    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = d;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < kThreads / 64; ++w) t += s_red[w];
+        h[static_cast<int64_t>(blockIdx.x) * l + blockIdx.y] = t;
+    }
+}
+
+// Symmetric eigen-decomposition of H (l x l, l even, fp64) by two-sided Jacobi with the round-robin
+// ordering: each round rotates l/2 disjoint index pairs at once.  One workgroup; H lives in LDS,
+// the eigenvectors P (columns) in global memory.  On exit lambda[i] = H[i][i] and order[k] is the
+// index of the k-th largest eigenvalue.
+__global__ void __launch_bounds__(kThreads)
+jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p, double* __restrict__ lambda,
+                  int* __restrict__ order, int sweeps)
+{
+    extern __shared__ double s_h[];                                   // [l][l], then c[l/2], s[l/2], pair[l]
+    double* const s_c = s_h + l * l;
+    double* const s_s = s_c + l / 2;
+    int* const s_pos = reinterpret_cast<int*>(s_s + l / 2);           // round-robin positions [l]
+    int* const s_pp = s_pos + l;                                      // pairs of this round: p[k], q[k]
+    for (int q = threadIdx.x; q < l * l; q += kThreads) {
+        s_h[q] = h_in[q];
+        p[q] = (q / l == q % l) ? 1.0 : 0.0;
+    }
+    for (int q = threadIdx.x; q < l; q += kThreads) s_pos[q] = q;
+    __syncthreads();
+    const int half = l / 2;
+    for (int sweep = 0; sweep < sweeps; ++sweep) {
+        for (int round = 0; round < l - 1; ++round) {
+            // pairs (pos[k], pos[l-1-k]) and their rotations from the current 2x2 blocks
+            for (int k = threadIdx.x; k < half; k += kThreads) {
+                int a = s_pos[k], b = s_pos[l - 1 - k];
+                if (a > b) { const int t = a; a = b; b = t; }
+                s_pp[2 * k] = a; s_pp[2 * k + 1] = b;
+                const double haa = s_h[a * l + a], hbb = s_h[b * l + b], hab = s_h[a * l + b];
+                double c = 1.0, s = 0.0;
+                if (fabs(hab) > 1e-300) {
+                    const double tau = (hbb - haa) / (2.0 * hab);
+                    const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+                    c = 1.0 / sqrt(1.0 + t * t);
+                    s = t * c;
+                }
+                s_c[k] = c; s_s[k] = s;
+            }
+            __syncthreads();
+            // columns: H <- H J, P <- P J   (pairs are disjoint, so all of them at once)
+            for (int q = threadIdx.x; q < half * l; q += kThreads) {
+                const int k = q / l, i = q - k * l;
+                const int a = s_pp[2 * k], b = s_pp[2 * k + 1];
+                const double c = s_c[k], s = s_s[k];
+                const double ha = s_h[i * l + a], hb = s_h[i * l + b];
+                s_h[i * l + a] = c * ha - s * hb;
+                s_h[i * l + b] = s * ha + c * hb;
+                const double pa = p[i * l + a], pb = p[i * l + b];
+                p[i * l + a] = c * pa - s * pb;
+                p[i * l + b] = s * pa + c * pb;
+            }
+            __syncthreads();
+            // rows: H <- J^T H
+            for (int q = threadIdx.x; q < half * l; q += kThreads) {
+                const int k = q / l, j = q - k * l;
+                const int a = s_pp[2 * k], b = s_pp[2 * k + 1];
+                const double c = s_c[k], s = s_s[k];
+                const double ha = s_h[a * l + j], hb = s_h[b * l + j];
+                s_h[a * l + j] = c * ha - s * hb;
+                s_h[b * l + j] = s * ha + c * hb;
+            }
+            __syncthreads();
+            // next round: position 0 stays, the others rotate by one
+            if (threadIdx.x == 0) {
+                const int last = s_pos[l - 1];
+                for (int q = l - 1; q > 1; --q) s_pos[q] = s_pos[q - 1];
+                s_pos[1] = last;
+            }
+            __syncthreads();
+        }
+    }
+    for (int i = threadIdx.x; i < l; i += kThreads) lambda[i] = s_h[i * l + i];
+    __syncthreads();
+    // rank by eigenvalue, larger first, equal values by smaller index
+    for (int i = threadIdx.x; i < l; i += kThreads) {
+        const double li = s_h[i * l + i];
+        int rank = 0;
+        for (int j = 0; j < l; ++j) {
+            const double lj = s_h[j * l + j];
+            rank += (lj > li || (lj == li && j < i)) ? 1 : 0;
+        }
+        order[rank] = i;
+    }
+}
+
+// A^[k][j] = lambda_k^(1/4) * sum_c P[c][order[k]] Z[c][j];  sigma[k] = sqrt(lambda_k)
+__global__ void __launch_bounds__(kThreads)
+rotate_kernel(const float* __restrict__ z, int l, int64_t n, const double* __restrict__ p,
+              const double* __restrict__ lambda, const int* __restrict__ order, int r,
+              float* __restrict__ a_out, float* __restrict__ sigma_out)
+{
+    const int k = blockIdx.y;
+    const int col = order[k];
+    const double lam = lambda[col] > 0.0 ? lambda[col] : 0.0;
+    const double scale = sqrt(sqrt(lam));
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (j < n) {
+        double acc = 0.0;
+        for (int c = 0; c < l; ++c) acc += p[c * l + col] * static_cast<double>(z[static_cast<int64_t>(c) * n + j]);
+        a_out[static_cast<int64_t>(k) * n + j] = static_cast<float>(scale * acc);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) sigma_out[k] = static_cast<float>(sqrt(lam));
+}
+
+}  // namespace
+
+hipError_t launch_init_residual(const float* w, const uint8_t* wq, const float* s_w, int64_t count, float* e,
+                                hipStream_t stream)
+{
+    int64_t blocks = (count / 4 + kThreads - 1) / kThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 8192) blocks = 8192;
+    init_residual_kernel<<<static_cast<unsigned>(blocks), kThreads, 0, stream>>>(w, wq, s_w, count, e);
+    return hipGetLastError();
+}
+
+SvdLayout svd_layout(int64_t m, int64_t n, int64_t r)
+{
+    const size_t l = static_cast<size_t>(r) + 8;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    SvdLayout L;
+    size_t off = 0;
+    L.z = off;      off = up(off + sizeof(float) * l * static_cast<size_t>(n));
+    L.y = off;      off = up(off + sizeof(float) * l * static_cast<size_t>(m));
+    L.h = off;      off = up(off + sizeof(double) * l * l);
+    L.p = off;      off = up(off + sizeof(double) * l * l);
+    L.lambda = off; off = up(off + sizeof(double) * l);
+    L.order = off;  off = up(off + sizeof(int) * l);
+    L.total = off;
+    return L;
+}
+
+hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega, int iters,
+                                   float* a_out, float* sigma_out, uint8_t* ws, hipStream_t stream)
+{
+    const int l = static_cast<int>(r) + 8;
+    const SvdLayout L = svd_layout(m, n, r);
+    float* z = reinterpret_cast<float*>(ws + L.z);
+    float* y = reinterpret_cast<float*>(ws + L.y);
+    double* h = reinterpret_cast<double*>(ws + L.h);
+    double* p = reinterpret_cast<double*>(ws + L.p);
+    double* lambda = reinterpret_cast<double*>(ws + L.lambda);
+    int* order = reinterpret_cast<int*>(ws + L.order);
+    const unsigned gm = static_cast<unsigned>((m + 63) / 64), gn = static_cast<unsigned>((n + 63) / 64);
+    hipError_t err;
+#define FQ_CHECK_LAUNCH() do { err = hipGetLastError(); if (err != hipSuccess) return err; } while (0)
+    copy_kernel<<<1024, kThreads, 0, stream>>>(omega, z, static_cast<int64_t>(l) * n);
+    FQ_CHECK_LAUNCH();
+    orthonormalize_rows_kernel<<<1, kOrthThreads, 0, stream>>>(z, l, n);
+    FQ_CHECK_LAUNCH();
+    for (int it = 0; it < iters; ++it) {
+        apply_e_kernel<<<gm, kThreads, 0, stream>>>(e, m, n, z, l, y);
+        FQ_CHECK_LAUNCH();
+        orthonormalize_rows_kernel<<<1, kOrthThreads, 0, stream>>>(y, l, m);
+        FQ_CHECK_LAUNCH();
+        apply_et_kernel<<<gn, kThreads, 0, stream>>>(e, m, n, y, l, z);
+        FQ_CHECK_LAUNCH();
+        orthonormalize_rows_kernel<<<1, kOrthThreads, 0, stream>>>(z, l, n);
+        FQ_CHECK_LAUNCH();
+    }
+    apply_e_kernel<<<gm, kThreads, 0, stream>>>(e, m, n, z, l, y);
+    FQ_CHECK_LAUNCH();
+    gram_kernel<<<dim3(l, l), kThreads, 0, stream>>>(y, l, m, h);
+    FQ_CHECK_LAUNCH();
+    const size_t lds = sizeof(double) * (static_cast<size_t>(l) * l + l) + sizeof(int) * 2 * static_cast<size_t>(l);
+    err = hipFuncSetAttribute(reinterpret_cast<const void*>(&jacobi_eig_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    jacobi_eig_kernel<<<1, kThreads, lds, stream>>>(h, l, p, lambda, order, 14);
+    FQ_CHECK_LAUNCH();
+    rotate_kernel<<<dim3(static_cast<unsigned>((n + kThreads - 1) / kThreads), static_cast<unsigned>(r)), kThreads, 0,
+                    stream>>>(z, l, n, p, lambda, order, static_cast<int>(r), a_out, sigma_out);
+    FQ_CHECK_LAUNCH();
+#undef FQ_CHECK_LAUNCH
+    return hipSuccess;
+}
+
+}  // namespace falqon

@@ -137,3 +137,23 @@ def test_optimizer_argument_validation(L):
     assert adam(m=0) == 2 and adam(r=8) == 2 and adam(r=512) == 2 and adam(step=0) == 2
     assert adam(b1=1.0) == 2 and adam(b2=-0.1) == 2 and adam(eps=0.0) == 2 and adam(ss=ok, mx=0.0) == 2
     assert adam(buf=odd) == 3 and adam(ss=odd) == 3
+
+
+def test_initialization_argument_validation(L):
+    ok, odd = 0x10000, 0x10004
+    res = L.falqon_init_residual
+    assert res(None, _vp(ok), _vp(ok), 64, 64, _vp(ok), None) == 1 and res(_vp(ok), _vp(ok), _vp(ok), 64, 64, None, None) == 1
+    assert res(_vp(ok), _vp(ok), _vp(ok), 0, 64, _vp(ok), None) == 2 and res(_vp(ok), _vp(ok), _vp(ok), 64, 66, _vp(ok), None) == 2
+    assert res(_vp(odd), _vp(ok), _vp(ok), 64, 64, _vp(ok), None) == 3
+    assert L.falqon_svd_workspace_bytes(4096, 4096, 64) > 72 * 4096 * 8
+    assert L.falqon_svd_workspace_bytes(4096, 4096, 128) == 0 and L.falqon_svd_workspace_bytes(4096, 4096, 20) == 0
+    assert L.falqon_svd_workspace_bytes(16, 4096, 16) == 0            # fewer rows than vectors
+    svd = L.falqon_svd_right_factor
+    wsb = L.falqon_svd_workspace_bytes(256, 256, 16)
+
+    def f(e=ok, m=256, n=256, r=16, om=ok, it=2, a=ok, sg=ok, ws=ok, wb=wsb):
+        return svd(_vp(e), m, n, r, _vp(om), it, _vp(a), _vp(sg), _vp(ws), wb, None)
+
+    assert f(e=None) == 1 and f(om=None) == 1 and f(a=None) == 1 and f(sg=None) == 1
+    assert f(r=12) == 2 and f(r=128) == 2 and f(m=254) == 2 and f(it=-1) == 2 and f(it=100) == 2
+    assert f(a=odd) == 3 and f(ws=None) == 5 and f(wb=wsb - 1) == 5
