@@ -93,6 +93,28 @@ class MeldedLoRALinear(torch.nn.Module):
         _b.quantize(a.float().contiguous(), _b.E4M3, self.wq[self.out_features:], s_tmp, ws, scale_in=self.s_w)
         self.delta_buf.zero_()
 
+    @torch.no_grad()
+    def init_from_weight(self, w: torch.Tensor, iters: int = 6, seed: int = 0) -> torch.Tensor:
+        """The whole initialization algorithm on the GPU: W~, s_w <- Q(W); E = DQ(W~) - W;
+        A^ <- right factor of the rank-r SVD of E; A~ <- cast(A^ * s_w); buffer <- 0.
+        Returns the Ritz values (approximate leading singular values of E)."""
+        dev = self.wq.device
+        m, n, r = self.out_features, self.in_features, self.rank
+        w32 = w.to(device=dev, dtype=torch.float32).contiguous()
+        ws = self._workspace(16)
+        _b.quantize(w32, _b.E4M3, self.wq[:m], self.s_w, ws)
+        e = torch.empty(m, n, dtype=torch.float32, device=dev)
+        _b.init_residual(w32, self.wq[:m], self.s_w, e)
+        omega = torch.randn(r + 8, n, device=dev, generator=torch.Generator(device=dev).manual_seed(seed))
+        a_hat = torch.empty(r, n, dtype=torch.float32, device=dev)
+        sigma = torch.empty(r, dtype=torch.float32, device=dev)
+        svd_ws = torch.empty(_b.svd_workspace_bytes(m, n, r), dtype=torch.uint8, device=dev)
+        _b.svd_right_factor(e, r, omega, iters, a_hat, sigma, svd_ws)
+        s_tmp = torch.zeros(1, dtype=torch.float32, device=dev)
+        _b.quantize(a_hat, _b.E4M3, self.wq[m:], s_tmp, ws, scale_in=self.s_w)
+        self.delta_buf.zero_()
+        return sigma
+
     def forward(self, x: torch.Tensor) -> torch.Tensor:
         return _MeldedFn.apply(x, self)
 

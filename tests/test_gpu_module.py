@@ -66,3 +66,23 @@ def test_decoder_block_trains_through_the_buffers():
         assert len(set(idx.tolist())) == k
         assert (p.wq[: p.out_features] != w0[: p.out_features]).any()
         assert (p.wq[p.out_features:] == w0[p.out_features:]).all()        # adapter rows are never written
+
+
+def test_module_initializes_itself_from_a_weight():
+    n, m, r, k = 512, 640, 32, 8
+    w = (np.random.default_rng(8).normal(size=(m, n)) * 0.02).astype(np.float32)
+    lin = MeldedLoRALinear(n, m, r, k)
+    sigma = lin.init_from_weight(torch.from_numpy(w), iters=8)
+    torch.cuda.synchronize()
+    ref = oracle.init_adapter(w, r)
+    assert np.array_equal(np_of(lin.wq[:m]), ref["wq"]) and np.float32(lin.s_w.item()).tobytes() == ref["s_w"].tobytes()
+    sg = np_of(sigma).astype(np.float64)
+    assert np.all(np.diff(sg) <= 0) and np.all(sg <= ref["sv"][:r] * (1 + 1e-4))
+    assert np.sum(sg ** 2) >= 0.9 * np.sum(ref["sv"][:r] ** 2)
+    # adapter rows: codes of a matrix with orthogonal rows of squared norm sigma_i, at the backbone's scale
+    a = oracle.fp8_decode(np_of(lin.wq[m:]), oracle.E4M3) / np.float64(ref["s_w"])
+    gram = a @ a.T
+    assert np.max(np.abs(np.diag(gram) - sg)) <= 0.02 * sg[0]         # FP8 rounding of the entries
+    off = gram - np.diag(np.diag(gram))
+    assert np.max(np.abs(off)) <= 0.05 * sg[0]
+    assert not lin.delta_buf.any()
