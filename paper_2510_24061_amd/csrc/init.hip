@@ -3,15 +3,15 @@
 // and the right factor of its rank-r truncated SVD,  A^ = sqrt(S_r) V_r^T  (line 5), which the
 // caller then casts with the backbone's scale (line 6, falqon_quantize with scale_in).
 //
-// This runs once per layer, before training; it is off the hot path and written for clarity, not
-// for the last microsecond.  The SVD is a randomized subspace iteration (the paper only says "SVD";
+// This runs once per layer, before training; it is off the hot path and written for clarity first.  The SVD is a randomized subspace iteration (the paper only says "SVD";
 // a truncated factor is all it needs):
-//   Z0 = orth(Omega)                         l = r + 8 rows of length n, Omega Gaussian (caller's)
+//   Z0 = orth(Omega)                         l = r + 8 rows of length n, Omega Gaussian (caller's);
+//                                            orth = Cholesky QR applied twice
 //   repeat q times:  Y = orth(Z E^T);  Z = orth(Y E)
 //   Y = Z E^T;  H = Y Y^T (l x l, fp64);  H = P diag(lambda) P^T  (cyclic Jacobi, fp64)
 //   A^[i,:] = lambda_i^(1/4) * sum_c P[c,i] Z[c,:]      for the r largest lambda_i = sigma_i^2
-// Products with E accumulate in fp32, everything l x l and every inner product of the
-// orthonormalisation in fp64.
+// Products with E accumulate in fp32; everything l x l (Gram matrices, Cholesky factors, the
+// eigenproblem) is fp64.
 #include "falqon_internal.h"
 
 namespace falqon {
@@ -46,18 +46,20 @@ copy_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t coun
 }
 
 constexpr int kMaxL = 128;                 // vectors in the subspace (r + 8 <= 128)
-constexpr int kPerThread = kMaxL / 4;      // vectors per thread in the two products
+constexpr int kVecGroup = 32;              // vectors per workgroup in the two products (grid.y groups)
+constexpr int kPerThread = kVecGroup / 4;  // vectors per thread
 
-// Y[c][i] = sum_j E[i][j] Z[c][j]:  a workgroup owns 64 rows of E and walks j in chunks of 32.
-// thread: row i = t % 64, vectors c = t / 64, t / 64 + 4, ...
+// Y[c][i] = sum_j E[i][j] Z[c][j]:  a workgroup owns 64 rows of E and 32 of the vectors
+// (blockIdx.y) and walks j in chunks of 32.  thread: row i = t % 64, vectors c0 + t / 64 + 4 u.
 __global__ void __launch_bounds__(kThreads)
 apply_e_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* __restrict__ z, int l,
                float* __restrict__ y)
 {
     __shared__ float s_e[64][33];
-    __shared__ float s_z[kMaxL][33];
+    __shared__ float s_z[kVecGroup][33];
     const int ti = threadIdx.x & 63, tg = threadIdx.x >> 6;
     const int64_t i0 = static_cast<int64_t>(blockIdx.x) * 64;
+    const int c0 = blockIdx.y * kVecGroup;
     float acc[kPerThread];
 #pragma unroll
     for (int u = 0; u < kPerThread; ++u) acc[u] = 0.0f;
@@ -68,26 +70,23 @@ apply_e_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* _
             const int64_t gi = i0 + row, gj = j0 + col;
             s_e[row][col] = (gi < m && gj < n) ? e[gi * n + gj] : 0.0f;
         }
-        for (int q = threadIdx.x; q < l * 32; q += kThreads) {
+        for (int q = threadIdx.x; q < kVecGroup * 32; q += kThreads) {
             const int c = q >> 5, col = q & 31;
             const int64_t gj = j0 + col;
-            s_z[c][col] = gj < n ? z[static_cast<int64_t>(c) * n + gj] : 0.0f;
+            s_z[c][col] = (c0 + c < l && gj < n) ? z[static_cast<int64_t>(c0 + c) * n + gj] : 0.0f;
         }
         __syncthreads();
 #pragma unroll 4
         for (int jj = 0; jj < 32; ++jj) {
             const float ev = s_e[ti][jj];
 #pragma unroll
-            for (int u = 0; u < kPerThread; ++u) {
-                const int c = tg + 4 * u;
-                if (c < l) acc[u] = fmaf(ev, s_z[c][jj], acc[u]);
-            }
+            for (int u = 0; u < kPerThread; ++u) acc[u] = fmaf(ev, s_z[tg + 4 * u][jj], acc[u]);
         }
     }
     if (i0 + ti < m) {
 #pragma unroll
         for (int u = 0; u < kPerThread; ++u) {
-            const int c = tg + 4 * u;
+            const int c = c0 + tg + 4 * u;
             if (c < l) y[static_cast<int64_t>(c) * m + i0 + ti] = acc[u];
         }
     }
@@ -99,9 +98,10 @@ apply_et_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* 
                 float* __restrict__ z)
 {
     __shared__ float s_e[32][65];
-    __shared__ float s_y[kMaxL][33];
+    __shared__ float s_y[kVecGroup][33];
     const int tj = threadIdx.x & 63, tg = threadIdx.x >> 6;
     const int64_t j0 = static_cast<int64_t>(blockIdx.x) * 64;
+    const int c0 = blockIdx.y * kVecGroup;
     float acc[kPerThread];
 #pragma unroll
     for (int u = 0; u < kPerThread; ++u) acc[u] = 0.0f;
@@ -112,77 +112,78 @@ apply_et_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* 
             const int64_t gi = i0 + row, gj = j0 + col;
             s_e[row][col] = (gi < m && gj < n) ? e[gi * n + gj] : 0.0f;
         }
-        for (int q = threadIdx.x; q < l * 32; q += kThreads) {
+        for (int q = threadIdx.x; q < kVecGroup * 32; q += kThreads) {
             const int c = q >> 5, row = q & 31;
             const int64_t gi = i0 + row;
-            s_y[c][row] = gi < m ? y[static_cast<int64_t>(c) * m + gi] : 0.0f;
+            s_y[c][row] = (c0 + c < l && gi < m) ? y[static_cast<int64_t>(c0 + c) * m + gi] : 0.0f;
         }
         __syncthreads();
 #pragma unroll 4
         for (int ii = 0; ii < 32; ++ii) {
             const float ev = s_e[ii][tj];
 #pragma unroll
-            for (int u = 0; u < kPerThread; ++u) {
-                const int c = tg + 4 * u;
-                if (c < l) acc[u] = fmaf(ev, s_y[c][ii], acc[u]);
-            }
+            for (int u = 0; u < kPerThread; ++u) acc[u] = fmaf(ev, s_y[tg + 4 * u][ii], acc[u]);
         }
     }
     if (j0 + tj < n) {
 #pragma unroll
         for (int u = 0; u < kPerThread; ++u) {
-            const int c = tg + 4 * u;
+            const int c = c0 + tg + 4 * u;
             if (c < l) z[static_cast<int64_t>(c) * n + j0 + tj] = acc[u];
         }
     }
 }
 
-// Orthonormalise the l rows of v[l][len] in place: classical Gram-Schmidt applied twice per row
-// (inner products in fp64), one workgroup of 1024 threads.  A row that vanishes is left as zeros.
-constexpr int kOrthThreads = 1024;
-
-__device__ __forceinline__ double block_sum(double x, double* s_red /* [16] */)
+// Orthonormalisation of the l rows of V[l][len] by Cholesky QR, applied twice: G = V V^T (fp64,
+// gram_kernel), G = L L^T, V <- L^-1 V by forward substitution.  Everything of size len runs over
+// the whole chip; only the l x l factorisation is one workgroup.  The second application brings the
+// rows to orthonormal at the precision they are stored in whenever cond(V) < 1e8, which a product
+// with E of a set of orthonormal vectors is far from reaching.  A row whose pivot is not positive
+// (a vector in the span of the earlier ones) is set to zero.
+//
+// Right-looking factorisation in LDS.  Output: the strict lower triangle of L, and on the diagonal
+// the reciprocal of the pivot (0 for a dropped row).
+__global__ void __launch_bounds__(kThreads)
+cholesky_kernel(const double* __restrict__ g, int l, double* __restrict__ lfac)
 {
-    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    extern __shared__ double s_l[];                                   // [l][l]
+    for (int q = threadIdx.x; q < l * l; q += kThreads) s_l[q] = g[q];
     __syncthreads();
-    if ((threadIdx.x & 63) == 0) s_red[threadIdx.x >> 6] = x;
-    __syncthreads();
-    double t = 0.0;
-    for (int w = 0; w < kOrthThreads / 64; ++w) t += s_red[w];
-    return t;
+    const double tiny = 1e-28 * fmax(s_l[0], 1e-300);
+    for (int c = 0; c < l; ++c) {
+        const double d = s_l[c * l + c];
+        const bool dead = !(d > tiny);
+        const double rinv = dead ? 0.0 : 1.0 / sqrt(d);
+        __syncthreads();                                              // everyone has read the pivot
+        for (int k = c + threadIdx.x; k < l; k += kThreads)
+            s_l[k * l + c] = (k == c) ? rinv : s_l[k * l + c] * rinv;
+        __syncthreads();
+        const int rem = l - 1 - c;                                    // trailing block, lower half only
+        for (int q = threadIdx.x; q < rem * rem; q += kThreads) {
+            const int k = c + 1 + q / rem, j = c + 1 + q % rem;
+            if (j <= k) s_l[k * l + j] -= s_l[k * l + c] * s_l[j * l + c];
+        }
+        __syncthreads();
+    }
+    for (int q = threadIdx.x; q < l * l; q += kThreads) lfac[q] = (q % l <= q / l) ? s_l[q] : 0.0;
 }
 
-__global__ void __launch_bounds__(kOrthThreads)
-orthonormalize_rows_kernel(float* __restrict__ v, int l, int64_t len)
+// V <- L^-1 V in place: one lane per column of V, rows solved in order; the column lives in LDS.
+__global__ void __launch_bounds__(64)
+solve_lower_kernel(float* __restrict__ v, int l, int64_t len, const double* __restrict__ lfac)
 {
-    __shared__ double s_dot[kMaxL];
-    __shared__ double s_red[kOrthThreads / 64];
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __shared__ float s_q[kMaxL][64];
+    const int tj = threadIdx.x;
+    const int64_t j = static_cast<int64_t>(blockIdx.x) * 64 + tj;
+    if (j >= len) return;                                             // no barrier below: a lane only touches its own column
+    for (int c = 0; c < l; ++c) s_q[c][tj] = v[static_cast<int64_t>(c) * len + j];
     for (int c = 0; c < l; ++c) {
-        float* vc = v + static_cast<int64_t>(c) * len;
-        for (int pass = 0; pass < 2; ++pass) {
-            // d_p = <v_c, v_p> for every p < c: wave w takes p = w, w + 16, ...
-            for (int p = wave; p < c; p += kOrthThreads / 64) {
-                const float* vp = v + static_cast<int64_t>(p) * len;
-                double d = 0.0;
-                for (int64_t j = lane; j < len; j += 64) d += static_cast<double>(vc[j]) * static_cast<double>(vp[j]);
-                for (int off = 32; off > 0; off >>= 1) d += __shfl_xor(d, off, 64);
-                if (lane == 0) s_dot[p] = d;
-            }
-            __syncthreads();
-            for (int64_t j = threadIdx.x; j < len; j += kOrthThreads) {
-                double x = static_cast<double>(vc[j]);
-                for (int p = 0; p < c; ++p) x -= s_dot[p] * static_cast<double>(v[static_cast<int64_t>(p) * len + j]);
-                vc[j] = static_cast<float>(x);
-            }
-            __syncthreads();
-        }
-        double nn = 0.0;
-        for (int64_t j = threadIdx.x; j < len; j += kOrthThreads) nn += static_cast<double>(vc[j]) * static_cast<double>(vc[j]);
-        nn = block_sum(nn, s_red);
-        const double inv = nn > 0.0 ? 1.0 / sqrt(nn) : 0.0;
-        for (int64_t j = threadIdx.x; j < len; j += kOrthThreads) vc[j] = static_cast<float>(static_cast<double>(vc[j]) * inv);
-        __syncthreads();
+        const double* row = lfac + static_cast<int64_t>(c) * l;
+        double acc = static_cast<double>(s_q[c][tj]);
+        for (int p = 0; p < c; ++p) acc -= row[p] * static_cast<double>(s_q[p][tj]);
+        const float q = static_cast<float>(acc * row[c]);
+        s_q[c][tj] = q;
+        v[static_cast<int64_t>(c) * len + j] = q;
     }
 }
 
@@ -207,7 +208,8 @@ gram_kernel(const float* __restrict__ y, int l, int64_t m, double* __restrict__ 
 
 // Symmetric eigen-decomposition of H (l x l, l even, fp64) by two-sided Jacobi with the round-robin
 // ordering: each round rotates l/2 disjoint index pairs at once.  One workgroup; H lives in LDS,
-// the eigenvectors P (columns) in global memory.  On exit lambda[i] = H[i][i] and order[k] is the
+// the eigenvectors P (columns) in global memory.  Stops after the first sweep without a rotation, or
+// after `sweeps`.  On exit lambda[i] = H[i][i] and order[k] is the
 // index of the k-th largest eigenvalue.
 __global__ void __launch_bounds__(kThreads)
 jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p, double* __restrict__ lambda,
@@ -218,6 +220,7 @@ jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p
     double* const s_s = s_c + l / 2;
     int* const s_pos = reinterpret_cast<int*>(s_s + l / 2);           // round-robin positions [l]
     int* const s_pp = s_pos + l;                                      // pairs of this round: p[k], q[k]
+    int* const s_rot = s_pp + l;                                      // rotations taken in this sweep
     for (int q = threadIdx.x; q < l * l; q += kThreads) {
         s_h[q] = h_in[q];
         p[q] = (q / l == q % l) ? 1.0 : 0.0;
@@ -226,6 +229,8 @@ jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p
     __syncthreads();
     const int half = l / 2;
     for (int sweep = 0; sweep < sweeps; ++sweep) {
+        if (threadIdx.x == 0) *s_rot = 0;
+        __syncthreads();
         for (int round = 0; round < l - 1; ++round) {
             // pairs (pos[k], pos[l-1-k]) and their rotations from the current 2x2 blocks
             for (int k = threadIdx.x; k < half; k += kThreads) {
@@ -234,7 +239,9 @@ jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p
                 s_pp[2 * k] = a; s_pp[2 * k + 1] = b;
                 const double haa = s_h[a * l + a], hbb = s_h[b * l + b], hab = s_h[a * l + b];
                 double c = 1.0, s = 0.0;
-                if (fabs(hab) > 1e-300) {
+                // an off-diagonal entry below the rounding level of its two diagonal ones is left alone
+                if (fabs(hab) > 1e-300 && fabs(hab) > 1e-16 * sqrt(fabs(haa * hbb))) {
+                    atomicAdd(s_rot, 1);
                     const double tau = (hbb - haa) / (2.0 * hab);
                     const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
                     c = 1.0 / sqrt(1.0 + t * t);
@@ -274,6 +281,8 @@ jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p
             }
             __syncthreads();
         }
+        if (*s_rot == 0) break;                                       // converged (same value in every lane)
+        __syncthreads();
     }
     for (int i = threadIdx.x; i < l; i += kThreads) lambda[i] = s_h[i * l + i];
     __syncthreads();
@@ -336,6 +345,23 @@ SvdLayout svd_layout(int64_t m, int64_t n, int64_t r)
     return L;
 }
 
+// rows of v[l][len] <- orthonormal (Cholesky QR twice); h and lfac are l x l fp64 scratch
+static hipError_t orthonormalize_rows(float* v, int l, int64_t len, double* h, double* lfac, hipStream_t stream)
+{
+    const size_t lds = sizeof(double) * static_cast<size_t>(l) * l;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(&cholesky_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    if (err != hipSuccess) return err;
+    for (int pass = 0; pass < 2; ++pass) {
+        gram_kernel<<<dim3(l, l), kThreads, 0, stream>>>(v, l, len, h);
+        cholesky_kernel<<<1, kThreads, lds, stream>>>(h, l, lfac);
+        solve_lower_kernel<<<static_cast<unsigned>((len + 63) / 64), 64, 0, stream>>>(v, l, len, lfac);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega, int iters,
                                    float* a_out, float* sigma_out, uint8_t* ws, hipStream_t stream)
 {
@@ -348,27 +374,28 @@ hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t
     double* lambda = reinterpret_cast<double*>(ws + L.lambda);
     int* order = reinterpret_cast<int*>(ws + L.order);
     const unsigned gm = static_cast<unsigned>((m + 63) / 64), gn = static_cast<unsigned>((n + 63) / 64);
+    const unsigned gv = static_cast<unsigned>((l + kVecGroup - 1) / kVecGroup);
     hipError_t err;
 #define FQ_CHECK_LAUNCH() do { err = hipGetLastError(); if (err != hipSuccess) return err; } while (0)
     copy_kernel<<<1024, kThreads, 0, stream>>>(omega, z, static_cast<int64_t>(l) * n);
     FQ_CHECK_LAUNCH();
-    orthonormalize_rows_kernel<<<1, kOrthThreads, 0, stream>>>(z, l, n);
-    FQ_CHECK_LAUNCH();
+    err = orthonormalize_rows(z, l, n, h, p, stream);
+    if (err != hipSuccess) return err;
     for (int it = 0; it < iters; ++it) {
-        apply_e_kernel<<<gm, kThreads, 0, stream>>>(e, m, n, z, l, y);
+        apply_e_kernel<<<dim3(gm, gv), kThreads, 0, stream>>>(e, m, n, z, l, y);
         FQ_CHECK_LAUNCH();
-        orthonormalize_rows_kernel<<<1, kOrthThreads, 0, stream>>>(y, l, m);
+        err = orthonormalize_rows(y, l, m, h, p, stream);
+        if (err != hipSuccess) return err;
+        apply_et_kernel<<<dim3(gn, gv), kThreads, 0, stream>>>(e, m, n, y, l, z);
         FQ_CHECK_LAUNCH();
-        apply_et_kernel<<<gn, kThreads, 0, stream>>>(e, m, n, y, l, z);
-        FQ_CHECK_LAUNCH();
-        orthonormalize_rows_kernel<<<1, kOrthThreads, 0, stream>>>(z, l, n);
-        FQ_CHECK_LAUNCH();
+        err = orthonormalize_rows(z, l, n, h, p, stream);
+        if (err != hipSuccess) return err;
     }
-    apply_e_kernel<<<gm, kThreads, 0, stream>>>(e, m, n, z, l, y);
+    apply_e_kernel<<<dim3(gm, gv), kThreads, 0, stream>>>(e, m, n, z, l, y);
     FQ_CHECK_LAUNCH();
     gram_kernel<<<dim3(l, l), kThreads, 0, stream>>>(y, l, m, h);
     FQ_CHECK_LAUNCH();
-    const size_t lds = sizeof(double) * (static_cast<size_t>(l) * l + l) + sizeof(int) * 2 * static_cast<size_t>(l);
+    const size_t lds = sizeof(double) * (static_cast<size_t>(l) * l + l) + sizeof(int) * (2 * static_cast<size_t>(l) + 4);
     err = hipFuncSetAttribute(reinterpret_cast<const void*>(&jacobi_eig_kernel),
                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
