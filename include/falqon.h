@@ -179,6 +179,23 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
                               void* c, falqon_dtype ct, void* stream);
 
 /*
+ * Measurement aid, not a step of the method: a register-only loop of the FP8 matrix-core
+ * instruction the products use (32x32x64, E4M3 x E4M3, fp32 accumulation).  Each of the
+ * `workgroups` x 4 waves fills its operand registers once (lane t reads bytes [128 t, 128 t + 128)
+ * of a_codes and of b_codes, so both must hold at least 8192 bytes), runs `iters` rounds of 16
+ * instructions, and writes the sum of its accumulators to sink[workgroup * 256 + thread].  A launch
+ * performs workgroups * 4 * iters * 16 * 2 * 32 * 32 * 64 floating-point operations with no memory
+ * traffic inside the loop: timed by the caller, that is the matrix-core rate the chip sustains for
+ * those operand bits, the ceiling a product kernel can be compared with besides the nominal peak.
+ *
+ *   a_codes, b_codes  in   E4M3 codes, device, 32-byte aligned, >= 8192 bytes each
+ *   sink              out  fp32 [workgroups * 256], device
+ * 1 <= workgroups <= 65536, 1 <= iters <= 1000000.
+ */
+falqon_status falqon_mfma_probe(const uint8_t* a_codes, const uint8_t* b_codes, int64_t workgroups, int64_t iters,
+                                float* sink, void* stream);
+
+/*
  * Optimizer step into the proxy buffer: "DeltaBuffer <- Optimizer(dL/dB, lr)", the second line of
  * the loop of the paper's backward-and-update algorithm, with the optimizer its experiments name
  * (AdamW with a maximum gradient norm of 0.3; "Detailed experimental settings").  Two calls:

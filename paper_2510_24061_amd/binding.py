@@ -54,6 +54,8 @@ def lib():
                                         f32p, f32p, c.c_float, vp, c.c_size_t, vp]
         L.falqon_proxy_update.restype = c.c_int
         L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
+        L.falqon_mfma_probe.restype = c.c_int
+        L.falqon_mfma_probe.argtypes = [vp, vp, i64, i64, vp, vp]
         L.falqon_fp8_gemm.restype = c.c_int
         L.falqon_fp8_gemm.argtypes = [vp, c.c_int, vp, c.c_int, i64, i64, i64, f32p, f32p, vp, c.c_int, vp]
         L.falqon_grad_sqnorm.restype = c.c_int
@@ -150,6 +152,15 @@ def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c) -> None:
     st = lib().falqon_fp8_gemm(_p(a), a_fmt, _p(b), 1 if b_is_kn else 0, M, N, K, _p(s_a), _p(s_b), _p(c),
                                _dtype_code(c), _stream())
     _check(st, "falqon_fp8_gemm")
+
+
+def mfma_probe(a_codes, b_codes, workgroups: int, iters: int, sink) -> None:
+    """Register-only FP8 matrix-core loop (measurement aid); workgroups*4*iters*16*2*32*32*64 flops per call."""
+    _dev(a_codes, b_codes, sink)
+    if a_codes.numel() < 8192 or b_codes.numel() < 8192 or sink.numel() < workgroups * 256:
+        raise ValueError("mfma_probe: operands need 8192 bytes each, sink workgroups*256 floats")
+    st = lib().falqon_mfma_probe(_p(a_codes), _p(b_codes), workgroups, iters, _p(sink), _stream())
+    _check(st, "falqon_mfma_probe")
 
 
 def grad_sqnorm(g, sum_sq, ws) -> None:

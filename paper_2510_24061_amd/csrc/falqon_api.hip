@@ -252,6 +252,18 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 
+falqon_status falqon_mfma_probe(const uint8_t* a_codes, const uint8_t* b_codes, int64_t workgroups, int64_t iters,
+                                float* sink, void* stream)
+{
+    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > 1000000) return FALQON_ERR_SHAPE;
+    if (!a_codes || !b_codes || !sink) return FALQON_ERR_NULL;
+    if ((reinterpret_cast<uintptr_t>(a_codes) & 31u) || (reinterpret_cast<uintptr_t>(b_codes) & 31u) || misaligned(sink))
+        return FALQON_ERR_ALIGN;
+    hipError_t e = launch_mfma_probe(a_codes, b_codes, static_cast<int>(workgroups), static_cast<int>(iters), sink,
+                                     static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
 falqon_status falqon_grad_sqnorm(const float* g, int64_t count, double* sum_sq,
                                  void* ws, size_t ws_bytes, void* stream)
 {

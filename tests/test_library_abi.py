@@ -157,3 +157,16 @@ def test_initialization_argument_validation(L):
     assert f(e=None) == 1 and f(om=None) == 1 and f(a=None) == 1 and f(sg=None) == 1
     assert f(r=12) == 2 and f(r=128) == 2 and f(m=254) == 2 and f(it=-1) == 2 and f(it=100) == 2
     assert f(a=odd) == 3 and f(ws=None) == 5 and f(wb=wsb - 1) == 5
+
+
+def test_mfma_probe_argument_validation(L):
+    p = L.falqon_mfma_probe
+    ok, odd = 0x10000, 0x10010                                      # 32-byte aligned / only 16-byte aligned
+    assert p(None, _vp(ok), 1, 1, _vp(ok), None) == 1
+    assert p(_vp(ok), _vp(ok), 1, 1, None, None) == 1
+    assert p(_vp(ok), _vp(ok), 0, 1, _vp(ok), None) == 2
+    assert p(_vp(ok), _vp(ok), 65537, 1, _vp(ok), None) == 2
+    assert p(_vp(ok), _vp(ok), 1, 0, _vp(ok), None) == 2
+    assert p(_vp(ok), _vp(ok), 1, 1000001, _vp(ok), None) == 2
+    assert p(_vp(odd), _vp(ok), 1, 1, _vp(ok), None) == 3
+    assert p(_vp(ok), _vp(odd), 1, 1, _vp(ok), None) == 3
