@@ -43,6 +43,7 @@ def lib():
                              p, c.c_int64, p, c.c_int64, p]
         L.orc_db.argtypes = [p, c.c_float, p, c.c_float, c.c_int64, c.c_int64, c.c_int64,
                              p, c.c_int64, p, p, p]
+        L.orc_db_wide.argtypes = [p, c.c_float, p, c.c_int64, c.c_int64, c.c_int64, p, c.c_int64, p]
         L.orc_delta_accumulate.argtypes = [p, p, c.c_int64, c.c_float]
         L.orc_adamw_delta.argtypes = [p, p, p, p, c.c_int64, c.c_int64, c.c_double, c.c_double, c.c_double,
                                       c.c_double, c.c_double]
@@ -156,6 +157,19 @@ def db(dyq, s_dy, o_a, amax_oa, rows=None):
     lib().orc_db(_ptr(dyq), float(s_dy), _ptr(oa), float(amax_oa), T, m, r,
                  _ptr(rs), nr, _ptr(out), _ptr(oaq), _ptr(s_oa))
     return out, oaq, np.float32(s_oa[0])
+
+
+def db_wide(dyq, s_dy, o_a, rows=None) -> np.ndarray:
+    """dB fp64 [rows, r] with O_A taken as given (16-bit values), not cast to E4M3."""
+    dyq = _c(dyq, np.uint8)
+    oa = _c(o_a, np.float32)
+    T, m = dyq.shape
+    r = oa.shape[1]
+    assert oa.shape[0] == T
+    rs, nr = _sel(rows)
+    out = np.empty((nr if rs is not None else m, r), np.float64)
+    lib().orc_db_wide(_ptr(dyq), float(s_dy), _ptr(oa), T, m, r, _ptr(rs), nr, _ptr(out))
+    return out
 
 
 def delta_accumulate(buf, d_b, lr) -> np.ndarray:

@@ -267,6 +267,34 @@ void orc_db(const uint8_t* dyq, float s_dy, const float* o_a, float amax_oa,
 }
 
 /* ------------------------------------------------------------------------- */
+/* The same adapter gradient with the saved O_A kept at its 16-bit precision  */
+/* (the paper does not say in which precision the operands of this small      */
+/* product are held; E5M2 values are exactly representable in bf16, so only   */
+/* the cast of O_A to E4M3 is dropped):                                       */
+/*   dB[i,p] = ( sum_t dec5(dyq[t,i]) * o_a[t,p] ) / s_dy                     */
+/* ------------------------------------------------------------------------- */
+void orc_db_wide(const uint8_t* dyq, float s_dy, const float* o_a,
+                 int64_t T, int64_t m, int64_t r,
+                 const int64_t* row_sel, int64_t n_rows, double* out)
+{
+    double lut5[256];
+    for (int c = 0; c < 256; ++c) lut5[c] = orc_fp8_decode((uint8_t)c, 1);
+    if (!row_sel) n_rows = m;
+    #pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t a = 0; a < n_rows; ++a) {
+        int64_t i = row_sel ? row_sel[a] : a;
+        double* acc = out + a * r;
+        for (int64_t p = 0; p < r; ++p) acc[p] = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            double g = lut5[dyq[t * m + i]];
+            const float* orow = o_a + t * r;
+            for (int64_t p = 0; p < r; ++p) acc[p] += g * (double)orow[p];
+        }
+        for (int64_t p = 0; p < r; ++p) acc[p] = acc[p] / (double)s_dy;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
 /* Proxy buffer accumulation: stand-in for "DeltaBuffer <- Optimizer(dB, lr)" */
 /* of the backward-and-update algorithm, as plain SGD on the change of B:     */
 /*   buf[i,p] = fl32( buf[i,p] + fl32( -lr * fl32(dB[i,p]) ) )                */

@@ -200,6 +200,50 @@ def test_db_from_forward_o_a_approximates_full_precision_adapter_gradient():
     assert _relf(b["dx"], ref_dx) < 0.12
 
 
+def test_db_wide_matches_numpy_exact_case_and_the_e4m3_variant_on_representable_o_a():
+    g = np.random.default_rng(17)
+    T, m, r = 37, 11, 5
+    dyq = _finite_codes(g, (T, m), oracle.E5M2)
+    o_a = oracle.round_bf16(g.normal(size=(T, r)) * 3)
+    s_dy = np.float32(77.0)
+    got = oracle.db_wide(dyq, s_dy, o_a)
+    want = _dec(dyq, T5).T @ o_a.astype(np.float64) / np.float64(s_dy)
+    assert got.shape == (m, r) and _relf(got, want) < 1e-14
+    rows = [10, 0, 3]
+    assert np.array_equal(oracle.db_wide(dyq, s_dy, o_a, rows), got[rows])
+    # small integers, power-of-two scale: exact
+    dy_small = np.array([[1, -2], [3, 0], [-1, 1]], np.float32)                          # [T=3, m=2]
+    oa_small = np.array([[2, 1, 0], [1, -1, 4], [0, 3, -2]], np.float32)                 # [T=3, r=3]
+    q5 = oracle.fp8_encode(dy_small * 4, oracle.E5M2)                                    # s_dy = 4
+    exact = oracle.db_wide(q5, np.float32(4.0), oa_small)
+    assert np.array_equal(exact, dy_small.astype(np.float64).T @ oa_small.astype(np.float64))
+    # an O_A that E4M3 represents exactly at its own scale: both variants must agree
+    codes = _finite_codes(g, (T, r), oracle.E4M3)
+    codes[0, 0] = 0x7E                                                                   # amax maps to 448: s_oa = 1
+    o_rep = _dec(codes, T4).astype(np.float32)
+    narrow, oaq, s_oa = oracle.db(dyq, s_dy, o_rep, np.float32(448.0))
+    assert s_oa == 1.0 and np.array_equal(oaq & 0x7F, codes & 0x7F)
+    assert _relf(oracle.db_wide(dyq, s_dy, o_rep), narrow) < 1e-14
+
+
+def test_db_wide_is_closer_to_the_unquantized_adapter_gradient():
+    d = workloads.make_inputs(T=256, n=64, m=48, r=8, seed=9)
+    x, w, a, dy = (d[k].float().numpy() for k in ("x", "w", "a", "dy"))
+    wq, s_w, _ = oracle.quantize(w, oracle.E4M3)
+    aq, _, _ = oracle.quantize(a, oracle.E4M3, scale_in=s_w)
+    wcat = np.concatenate([wq, aq])
+    f = oracle.layer_fwd(x, wcat, s_w, 48, 8)
+    b = oracle.layer_bwd(dy, wcat, s_w, f["o_a"], f["amax_oa"], 48, 8)
+    wide = oracle.db_wide(b["dyq"], b["s_dy"], f["o_a"])
+    ref = _dec(b["dyq"], T5).T @ f["o_a"].astype(np.float64) / np.float64(b["s_dy"])
+    assert _relf(wide, ref) < 1e-14
+    # against the same E5M2 gradient times the fp64 O_A before its bf16 rounding
+    o_exact = (_dec(f["xq"], T4) @ _dec(aq, T4).T) / (np.float64(f["s_x"]) * np.float64(s_w))
+    ideal = _dec(b["dyq"], T5).T @ o_exact / np.float64(b["s_dy"])
+    assert _relf(wide, ideal) < _relf(b["db"], ideal)
+    assert _relf(wide, ideal) < 4e-3
+
+
 def test_delta_accumulate_closed_form():
     buf = np.array([[0.0, 1.0], [-2.0, 1e-3]], np.float32)
     d_b = np.array([[10.0, -5.0], [0.5, 1.0 / 3.0]], np.float64)
