@@ -377,6 +377,10 @@ def main():
     layer.adamw_step(1, sum_sq)                       # allocates the moments
     ms_sqnorm = _time_region(lambda: fq.grad_sqnorm(layer.d_b, sum_sq, layer.ws), it)
     ms_adamw = _time_region(lambda: layer.adamw_step(2, sum_sq), it)
+    # variant of the adapter gradient with O_A kept in bf16 (its two launches, outside the paired launch)
+    db_tmp = torch.empty(m, r, device="cuda")
+    ms_db_wide = _time_region(lambda: fq.db_bf16(layer.dyq, layer.s_dy, layer.o_a, db_tmp, None, 0.0, layer.ws), it)
+    del db_tmp
     layer.delta_buf.zero_()
     s_tmp = torch.zeros(1, device="cuda")
     ms_quant = _time_region(lambda: fq.quantize(x, fq.E4M3, layer.xq, s_tmp, layer.ws), it)
@@ -418,6 +422,9 @@ def main():
         "adamw_buffer_step": {"grad_sqnorm_ms": ms_sqnorm, "adamw_delta_ms": ms_adamw,
                               "bytes": 28.0 * m * r, "GB/s": 28.0 * m * r / (ms_adamw * 1e-3) / 1e9,
                               "note": "optional replacement of the SGD buffer step inside melded_bwd; not in the timed step"},
+        "db_bf16_variant": {"ms": ms_db_wide, "flops": flops_db,
+                            "note": "dB = dy~^T O_A with O_A kept in bf16 (bf16 matrix cores), partial pass + ordered sum as "
+                                    "two launches of their own; not in the timed step"},
         "fwd_after_quantize": {"ms_derived": ms_fwd - ms_quant, "flops": 2.0 * T * n * (m + r),
                                "TFLOP/s": 2.0 * T * n * (m + r) / ((ms_fwd - ms_quant) * 1e-3) / 1e12,
                                "note": "melded_fwd minus the quantizer: gemm_fwd_pair_kernel (backbone tiles + adapter "

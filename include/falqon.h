@@ -179,6 +179,28 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
                               void* c, falqon_dtype ct, void* stream);
 
 /*
+ * Variant of the adapter gradient in falqon_melded_bwd (modified LoRA-backward equation, first line
+ * of the backward-and-update loop) that keeps the saved O_A at its 16-bit precision; the paper does
+ * not fix the precision of this small product's operands:
+ *   d_b[i,p] = ( sum_t value_E5M2(dyq[t,i]) * o_a[t,p] ) / s_dy          (fp32 accumulation)
+ *   delta_buf != NULL:  delta_buf += -lr * d_b
+ * E5M2 values are exact in bf16, so nothing is rounded before the accumulation.  dyq and s_dy are
+ * the ones falqon_melded_bwd returned; a caller that wants this gradient calls falqon_melded_bwd
+ * with delta_buf = NULL and then this function, which overwrites d_b and takes the buffer step.
+ *
+ *   dyq        in   E5M2 [T, m]
+ *   s_dy       in   device scalar
+ *   o_a        in   bf16 [T, r]
+ *   d_b        out  fp32 [m, r]
+ *   delta_buf  i/o  fp32 [m, r], nullable
+ *   ws         at least falqon_workspace_bytes(T, 16, m, r)
+ * Shapes as for falqon_melded_bwd.
+ */
+falqon_status falqon_db_bf16(const uint8_t* dyq, const float* s_dy, const void* o_a,
+                             int64_t T, int64_t m, int64_t r, float* d_b, float* delta_buf, float lr,
+                             void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Measurement aid, not a step of the method: a register-only loop of the FP8 matrix-core
  * instruction the products use (32x32x64, E4M3 x E4M3, fp32 accumulation).  Each of the
  * `workgroups` x 4 waves fills its operand registers once (lane t reads bytes [128 t, 128 t + 128)

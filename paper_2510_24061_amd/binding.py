@@ -54,6 +54,8 @@ def lib():
                                         f32p, f32p, c.c_float, vp, c.c_size_t, vp]
         L.falqon_proxy_update.restype = c.c_int
         L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
+        L.falqon_db_bf16.restype = c.c_int
+        L.falqon_db_bf16.argtypes = [vp, f32p, vp, i64, i64, i64, vp, vp, c.c_float, vp, c.c_size_t, vp]
         L.falqon_mfma_probe.restype = c.c_int
         L.falqon_mfma_probe.argtypes = [vp, vp, i64, i64, vp, vp]
         L.falqon_fp8_gemm.restype = c.c_int
@@ -152,6 +154,19 @@ def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c) -> None:
     st = lib().falqon_fp8_gemm(_p(a), a_fmt, _p(b), 1 if b_is_kn else 0, M, N, K, _p(s_a), _p(s_b), _p(c),
                                _dtype_code(c), _stream())
     _check(st, "falqon_fp8_gemm")
+
+
+def db_bf16(dyq, s_dy, o_a, d_b, delta_buf, lr: float, ws) -> None:
+    """d_b = dyq^T o_a / s_dy with O_A kept in bf16 (variant of the adapter gradient); optional buffer step."""
+    _dev(dyq, s_dy, o_a, d_b, ws)
+    if delta_buf is not None:
+        _dev(delta_buf)
+    T, m = dyq.shape
+    r = o_a.shape[1]
+    st = lib().falqon_db_bf16(_p(dyq), _p(s_dy), _p(o_a), T, m, r, _p(d_b),
+                              _p(delta_buf) if delta_buf is not None else None, float(lr), _p(ws),
+                              ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_db_bf16")
 
 
 def mfma_probe(a_codes, b_codes, workgroups: int, iters: int, sink) -> None:

@@ -29,6 +29,15 @@ db_partial_kernel(const DbArgs d)
     db_partial_tile(d, blockIdx.x, blockIdx.y, blockIdx.z, s_tiles, g_zero16);
 }
 
+// buf + fl32(-lr * g): product and sum are rounded separately, as the step is defined.  The
+// rounding intrinsics do not stop the compiler from fusing the pair, the pragma does.
+__device__ __forceinline__ float buffer_step(float buf, float lr, float g)
+{
+#pragma clang fp contract(off)
+    const float step = -lr * g;
+    return buf + step;
+}
+
 // dB = (sum of partials, split ascending) / (s_dy * s_oa);  delta_buf += -lr * dB
 template <int SPLITS>
 __global__ void __launch_bounds__(kThreads)
@@ -36,7 +45,7 @@ db_reduce_kernel(const float* __restrict__ partial, int64_t count,
                  const float* __restrict__ s_dy, const float* __restrict__ amax_oa,
                  float* __restrict__ d_b, float* delta_buf, float lr)
 {
-    const float s_oa_scale = 448.0f / fmaxf(*amax_oa, 1e-12f);
+    const float s_oa_scale = amax_oa ? 448.0f / fmaxf(*amax_oa, 1e-12f) : 1.0f;    // no amax: O_A was not cast
     const float inv = 1.0f / ((*s_dy) * s_oa_scale);
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * 4;
     for (int64_t e = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4; e < count; e += stride) {
@@ -61,10 +70,10 @@ db_reduce_kernel(const float* __restrict__ partial, int64_t count,
         *reinterpret_cast<float4*>(d_b + e) = s;
         if (delta_buf) {
             float4 d = *reinterpret_cast<const float4*>(delta_buf + e);
-            d.x = __fadd_rn(d.x, __fmul_rn(-lr, s.x));
-            d.y = __fadd_rn(d.y, __fmul_rn(-lr, s.y));
-            d.z = __fadd_rn(d.z, __fmul_rn(-lr, s.z));
-            d.w = __fadd_rn(d.w, __fmul_rn(-lr, s.w));
+            d.x = buffer_step(d.x, lr, s.x);
+            d.y = buffer_step(d.y, lr, s.y);
+            d.z = buffer_step(d.z, lr, s.z);
+            d.w = buffer_step(d.w, lr, s.w);
             *reinterpret_cast<float4*>(delta_buf + e) = d;
         }
     }

@@ -212,6 +212,26 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 
+falqon_status falqon_db_bf16(const uint8_t* dyq, const float* s_dy, const void* o_a,
+                             int64_t T, int64_t m, int64_t r, float* d_b, float* delta_buf, float lr,
+                             void* ws, size_t ws_bytes, void* stream)
+{
+    if (bad_layer_shape(T, 16, m, r)) return FALQON_ERR_SHAPE;
+    if (!dyq || !s_dy || !o_a || !d_b) return FALQON_ERR_NULL;
+    if (misaligned(dyq) || misaligned(o_a) || misaligned(d_b) || (delta_buf && misaligned(delta_buf)) ||
+        (reinterpret_cast<uintptr_t>(s_dy) & 3u))
+        return FALQON_ERR_ALIGN;
+    const WsLayout L = ws_layout(T, 16, m, r);
+    if (!ws || ws_bytes < L.total) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const DbArgs d = make_db_args(dyq, o_a, nullptr, T, m, r,
+                                  reinterpret_cast<float*>(static_cast<uint8_t*>(ws) + L.db_partials), db_splits(T, m));
+    hipError_t e = launch_db_wide_partial(d, st);
+    if (e == hipSuccess) e = launch_db_reduce(d, s_dy, d_b, delta_buf, lr, st);
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
 falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
                                   int32_t* idx_out, int clear_selected,
                                   void* ws, size_t ws_bytes, void* stream)

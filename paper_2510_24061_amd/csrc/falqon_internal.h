@@ -75,6 +75,8 @@ DbArgs make_db_args(const uint8_t* dyq, const void* o_a, const float* amax_oa, i
 hipError_t launch_db_partial(const DbArgs& d, hipStream_t stream);
 hipError_t launch_db_reduce(const DbArgs& d, const float* s_dy, float* d_b, float* delta_buf, float lr,
                             hipStream_t stream);
+// Variant with O_A kept in bf16 (db_wide.hip): d.amax_oa is not read and may be null, also in the reduce.
+hipError_t launch_db_wide_partial(const DbArgs& d, hipStream_t stream);
 // Input-gradient GEMM g ([K,N] right operand, E5M2 left operand, 256x256 tiles) and the partial pass
 // of the adapter gradient in one launch: both read only dy~ (and O_A, the weight).
 bool gemm_dx_db_pair_supported(const GemmArgs& g);

@@ -136,6 +136,9 @@ def _check_backward(T, n, m, r, k, d, wcat, s_w, out_dtype, n_sample=96):
     assert relf(np_of(layer.d_b), db_ref) < TOL
     buf_ref = oracle.delta_accumulate(buf0, db_ref, lr)
     assert relf(np_of(layer.delta_buf) - buf0, buf_ref - buf0) < TOL
+    # the step itself is two separately rounded fp32 operations on the gradient the call returned: bit-exact
+    assert np.array_equal(np_of(layer.delta_buf),
+                          oracle.delta_accumulate(buf0, np_of(layer.d_b).astype(np.float64), np.float32(lr)))
     return layer
 
 

@@ -170,3 +170,20 @@ def test_mfma_probe_argument_validation(L):
     assert p(_vp(ok), _vp(ok), 1, 1000001, _vp(ok), None) == 2
     assert p(_vp(odd), _vp(ok), 1, 1, _vp(ok), None) == 3
     assert p(_vp(ok), _vp(odd), 1, 1, _vp(ok), None) == 3
+
+
+def test_db_bf16_argument_validation(L):
+    f = L.falqon_db_bf16
+    ok, odd = 0x10000, 0x10004
+    big = L.falqon_workspace_bytes(64, 16, 64, 16)
+    import ctypes as c
+    lr = c.c_float(0.0)
+    assert f(None, _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), None, lr, _vp(ok), big, None) == 1
+    assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 16, None, None, lr, _vp(ok), big, None) == 1
+    assert f(_vp(ok), _vp(ok), _vp(ok), 0, 64, 16, _vp(ok), None, lr, _vp(ok), big, None) == 2
+    assert f(_vp(ok), _vp(ok), _vp(ok), 64, 40, 16, _vp(ok), None, lr, _vp(ok), big, None) == 2
+    assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 272, _vp(ok), None, lr, _vp(ok), big, None) == 2
+    assert f(_vp(odd), _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), None, lr, _vp(ok), big, None) == 3
+    assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), _vp(odd), lr, _vp(ok), big, None) == 3
+    assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), None, lr, None, big, None) == 5
+    assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), None, lr, _vp(ok), big - 1, None) == 5
