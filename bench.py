@@ -364,20 +364,22 @@ def main():
     ms_gemm_fwd = _time_region(lambda: fq.fp8_gemm(layer.xq, fq.E4M3, layer.wq[:m], False, layer.s_x, layer.s_w, y_tmp), it)
     ms_gemm_dx = _time_region(lambda: fq.fp8_gemm(layer.dyq, fq.E5M2, layer.wq[:m], True, layer.s_dy, layer.s_w,
                                                   layer.dx), it)
-    # the same launch on constant operands (every code = 1.0): identical instruction stream and memory traffic,
-    # but almost no switching in the multipliers, so the chip holds its full clock - the rate the kernel's
-    # schedule reaches when the power management does not intervene
-    ones_x, ones_w = torch.full_like(layer.xq, 0x38), torch.full_like(layer.wq[:m], 0x38)
-    ms_gemm_const = _time_region(lambda: fq.fp8_gemm(ones_x, fq.E4M3, ones_w, False, layer.s_x, layer.s_w, y_tmp), it)
-    del ones_x, ones_w
-    # the same matrix-core work as one backbone product (256 workgroups x 4 waves x 64 rounds x 16 instructions
-    # of 32x32x64) from registers only, on the workload's own codes: the rate the chip sustains with no memory
-    # traffic at all for these operand bits (its clock under matrix-core load falls as the bits toggle more)
-    sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
-    probe_rounds = n // 64
-    ms_probe = _time_region(lambda: fq.mfma_probe(layer.xq, layer.wq, 256, probe_rounds, sink), it)
-    tflops_probe = 256 * 4 * probe_rounds * 16 * 2.0 * 32 * 32 * 64 / (ms_probe * 1e-3) / 1e12
-    del sink
+    ms_gemm_const = ms_probe = tflops_probe = None
+    if not args.no_context:
+        # the same launch on constant operands (every code = 1.0): identical instruction stream and memory traffic,
+        # but almost no switching in the multipliers, so the chip holds its full clock - the rate the kernel's
+        # schedule reaches when the power management does not intervene
+        ones_x, ones_w = torch.full_like(layer.xq, 0x38), torch.full_like(layer.wq[:m], 0x38)
+        ms_gemm_const = _time_region(lambda: fq.fp8_gemm(ones_x, fq.E4M3, ones_w, False, layer.s_x, layer.s_w, y_tmp), it)
+        del ones_x, ones_w
+        # the same matrix-core work as one backbone product (256 workgroups x 4 waves x 64 rounds x 16 instructions
+        # of 32x32x64) from registers only, on the workload's own codes: the rate the chip sustains with no memory
+        # traffic at all for these operand bits (its clock under matrix-core load falls as the bits toggle more)
+        sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+        probe_rounds = n // 64
+        ms_probe = _time_region(lambda: fq.mfma_probe(layer.xq, layer.wq, 256, probe_rounds, sink), it)
+        tflops_probe = 256 * 4 * probe_rounds * 16 * 2.0 * 32 * 32 * 64 / (ms_probe * 1e-3) / 1e12
+        del sink
     # optimizer variant of the buffer step: bwd without the SGD step, global-norm term, AdamW into the buffer
     sum_sq = torch.zeros(1, dtype=torch.float64, device="cuda")
     layer.adamw_step(1, sum_sq)                       # allocates the moments
@@ -410,19 +412,18 @@ def main():
     roofline = {"bound": "mfma", "kernel": "gemm_fp8_kernel<2,2,4,4,false,0> (forward, X~ . W~^T, 256 tiles of 256x256)",
                 "achieved": tflops_fwd, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": tflops_fwd / FP8_PEAK_TFLOPS, "traffic": GEMM_FWD_TRAFFIC_BYTES,
-                "flops_per_launch": flops_fwd, "avg_launch_ms": ms_gemm_fwd,
-                "same_launch_constant_operands": {"ms": ms_gemm_const,
-                                                  "TFLOP/s": flops_fwd / (ms_gemm_const * 1e-3) / 1e12,
-                                                  "frac": flops_fwd / (ms_gemm_const * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
-                                                  "note": "same kernel, grid and traffic with all codes = 1.0: the clock "
-                                                          "stays at its nominal value; the gap to 'achieved' is the "
-                                                          "clock the chip grants for the workload's operand bits"},
-                "register_only_mfma_loop": {"TFLOP/s": tflops_probe, "ms": ms_probe,
-                                            "frac_of_peak": tflops_probe / FP8_PEAK_TFLOPS,
-                                            "achieved_over_loop": tflops_fwd / tflops_probe,
-                                            "note": "same instruction count as the product, operands = this workload's "
-                                                    "FP8 codes held in registers, no LDS/cache/HBM traffic: what the "
-                                                    "chip's power management lets the matrix cores sustain"}}
+                "flops_per_launch": flops_fwd, "avg_launch_ms": ms_gemm_fwd}
+    if not args.no_context:
+        roofline["same_launch_constant_operands"] = {
+            "ms": ms_gemm_const, "TFLOP/s": flops_fwd / (ms_gemm_const * 1e-3) / 1e12,
+            "frac": flops_fwd / (ms_gemm_const * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
+            "note": "same kernel, grid and traffic with all codes = 1.0: the clock stays at its nominal value; the gap "
+                    "to 'achieved' is the clock the chip grants for the workload's operand bits"}
+        roofline["register_only_mfma_loop"] = {
+            "TFLOP/s": tflops_probe, "ms": ms_probe, "frac_of_peak": tflops_probe / FP8_PEAK_TFLOPS,
+            "achieved_over_loop": tflops_fwd / tflops_probe,
+            "note": "same instruction count as the product, operands = this workload's FP8 codes held in registers, "
+                    "no LDS/cache/HBM traffic: what the chip's power management lets the matrix cores sustain"}
     kernels = {
         "gemm_fwd": {"ms": ms_gemm_fwd, "TFLOP/s": tflops_fwd, "frac_fp8_peak": tflops_fwd / FP8_PEAK_TFLOPS},
         "gemm_dx": {"ms": ms_gemm_dx, "TFLOP/s": tflops_dx, "frac_fp8_peak": tflops_dx / FP8_PEAK_TFLOPS},
