@@ -100,10 +100,11 @@ falqon_status falqon_quantize(const void* x, falqon_dtype xt, int64_t rows, int6
  *   o_a       = bf16( O_merged[:, m:] )             saved for the backward pass
  *   amax_oa   = max |o_a|
  *
- *   x        in   bf16 [T, n]
+ *   x        in   bf16 [T, n]; NULL: the first line is skipped and xq, s_x are inputs (layers that
+ *                 read the same activation, such as the q, k and v projections, quantize it once)
  *   wq       in   E4M3 [(m+r), n]: m backbone rows, then the r adapter rows cast with s_w
  *   s_w      in   device scalar, the backbone's scale
- *   xq, s_x  out  E4M3 [T, n] and its scale (the operands the product was formed from)
+ *   xq, s_x  out  E4M3 [T, n] and its scale (the operands the product was formed from); in if x is NULL
  *   y        out  [T, m] of dtype yt
  *   o_a      out  bf16 [T, r]
  *   amax_oa  out  device scalar

@@ -122,9 +122,10 @@ def quantize(x: torch.Tensor, fmt: int, q: torch.Tensor, scale_out: torch.Tensor
 
 
 def melded_fwd(x, wq, s_w, m: int, r: int, xq, s_x, y, o_a, amax_oa, ws) -> None:
+    """x = None: xq and s_x are inputs (already quantized by another layer's call or by quantize())."""
     _dev(x, wq, s_w, xq, s_x, y, o_a, amax_oa, ws)
-    T, n = x.shape
-    st = lib().falqon_melded_fwd(_p(x), _p(wq), _p(s_w), T, n, m, r, _p(xq), _p(s_x), _p(y), _dtype_code(y),
+    T, n = xq.shape
+    st = lib().falqon_melded_fwd(_p(x) if x is not None else None, _p(wq), _p(s_w), T, n, m, r, _p(xq), _p(s_x), _p(y), _dtype_code(y),
                                  _p(o_a), _p(amax_oa), _p(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_melded_fwd")
 

@@ -99,8 +99,8 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
 {
     if (yt != FALQON_BF16 && yt != FALQON_F32) return FALQON_ERR_ENUM;
     if (bad_layer_shape(T, n, m, r)) return FALQON_ERR_SHAPE;
-    if (!x || !wq || !s_w || !xq || !s_x || !y || !o_a || !amax_oa) return FALQON_ERR_NULL;
-    if (misaligned(x) || misaligned(wq) || misaligned(xq) || misaligned(y) || misaligned(o_a))
+    if (!wq || !s_w || !xq || !s_x || !y || !o_a || !amax_oa) return FALQON_ERR_NULL;     // x may be NULL
+    if ((x && misaligned(x)) || misaligned(wq) || misaligned(xq) || misaligned(y) || misaligned(o_a))
         return FALQON_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(s_w) & 3u) || (reinterpret_cast<uintptr_t>(s_x) & 3u) ||
         (reinterpret_cast<uintptr_t>(amax_oa) & 3u))
@@ -111,10 +111,12 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* w8 = static_cast<uint8_t*>(ws);
 
-    // x~, s_x <- Q_E4M3(x); the cast pass also resets the running maximum of O_A
-    hipError_t e = launch_quantize(x, FALQON_BF16, T, n, n, FALQON_E4M3, nullptr, xq, n, s_x, nullptr,
-                                   reinterpret_cast<float*>(w8 + L.amax_partials),
-                                   reinterpret_cast<uint32_t*>(amax_oa), st);
+    // x~, s_x <- Q_E4M3(x); the cast pass also resets the running maximum of O_A.  Without x the
+    // caller's x~ and s_x are used as they are (several layers reading one input quantize it once).
+    hipError_t e = x ? launch_quantize(x, FALQON_BF16, T, n, n, FALQON_E4M3, nullptr, xq, n, s_x, nullptr,
+                                       reinterpret_cast<float*>(w8 + L.amax_partials),
+                                       reinterpret_cast<uint32_t*>(amax_oa), st)
+                     : launch_zero_word(reinterpret_cast<uint32_t*>(amax_oa), st);
     if (e != hipSuccess) return FALQON_ERR_HIP;
 
     // O_merged <- x~ W~'^T / (s_w s_x), split into y and O_A.  When the r adapter columns fit

@@ -32,6 +32,8 @@ hipError_t launch_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t
                            falqon_fmt fmt, const float* scale_in, uint8_t* q, int64_t ld_q,
                            float* scale_out, float* amax_out, float* partials, uint32_t* zero_word,
                            hipStream_t stream);
+// Clears one device word with a kernel (a memset node is not safe inside a captured graph here).
+hipError_t launch_zero_word(uint32_t* w, hipStream_t stream);
 
 // ---- FP8 GEMMs (gemm.hip) ----------------------------------------------------------------
 // C[M,N] = A[M,K] . op(B) * 1 / (sa * sb), fp32 accumulation on the FP8 matrix cores.

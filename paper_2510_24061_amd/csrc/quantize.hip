@@ -139,6 +139,8 @@ scale_cast_kernel(const T* __restrict__ x, int64_t n_vecs, int64_t vecs_per_row,
     }
 }
 
+__global__ void zero_word_kernel(uint32_t* w) { *w = 0u; }
+
 template <typename T>
 hipError_t run(const T* x, int64_t rows, int64_t cols, int64_t ld_x, falqon_fmt fmt, const float* scale_in,
                uint8_t* q, int64_t ld_q, float* scale_out, float* amax_out, float* partials,
@@ -170,6 +172,12 @@ hipError_t run(const T* x, int64_t rows, int64_t cols, int64_t ld_x, falqon_fmt 
 }
 
 }  // namespace
+
+hipError_t launch_zero_word(uint32_t* w, hipStream_t stream)
+{
+    zero_word_kernel<<<1, 1, 0, stream>>>(w);
+    return hipGetLastError();
+}
 
 hipError_t launch_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t cols, int64_t ld_x,
                            falqon_fmt fmt, const float* scale_in, uint8_t* q, int64_t ld_q,

@@ -53,6 +53,73 @@ class _MeldedFn(torch.autograd.Function):
         return dx.reshape(*ctx.lead, layer.in_features), None
 
 
+class _MeldedGroupFn(torch.autograd.Function):
+    """Several layers that read the same activation: the input is quantized once, every layer's
+    product runs on those codes, and the input gradients are added."""
+
+    @staticmethod
+    def forward(ctx, x: torch.Tensor, group: "MeldedGroup"):
+        layers = group.layers
+        first = layers[0]
+        lead = x.shape[:-1]
+        x2 = x.reshape(-1, first.in_features)
+        if x2.dtype != torch.bfloat16:
+            x2 = x2.to(torch.bfloat16)
+        x2 = x2.contiguous()
+        T, dev = x2.shape[0], x2.device
+        xq = torch.empty(T, first.in_features, dtype=torch.uint8, device=dev)
+        s_x = torch.empty(1, dtype=torch.float32, device=dev)
+        _b.quantize(x2, _b.E4M3, xq, s_x, first._workspace(T))
+        outs, saved = [], []
+        for layer in layers:
+            y = torch.empty(T, layer.out_features, dtype=torch.bfloat16, device=dev)
+            o_a = torch.empty(T, layer.rank, dtype=torch.bfloat16, device=dev)
+            amax_oa = torch.empty(1, dtype=torch.float32, device=dev)
+            _b.melded_fwd(None, layer.wq, layer.s_w, layer.out_features, layer.rank, xq, s_x, y, o_a, amax_oa,
+                          layer._workspace(T))
+            outs.append(y.reshape(*lead, layer.out_features))
+            saved += [o_a, amax_oa]
+        ctx.group, ctx.T, ctx.lead = group, T, lead
+        ctx.save_for_backward(*saved)
+        return tuple(outs)
+
+    @staticmethod
+    def backward(ctx, *dys):
+        layers, T = ctx.group.layers, ctx.T
+        saved = ctx.saved_tensors
+        total = None
+        for i, (layer, dy) in enumerate(zip(layers, dys)):
+            o_a, amax_oa = saved[2 * i], saved[2 * i + 1]
+            dev = o_a.device
+            if dy is None:
+                dy2 = torch.zeros(T, layer.out_features, dtype=torch.bfloat16, device=dev)
+            else:
+                dy2 = dy.reshape(T, layer.out_features)
+                if dy2.dtype != torch.bfloat16:
+                    dy2 = dy2.to(torch.bfloat16)
+                dy2 = dy2.contiguous()
+            dyq = torch.empty(T, layer.out_features, dtype=torch.uint8, device=dev)
+            s_dy = torch.empty(1, dtype=torch.float32, device=dev)
+            dx = torch.empty(T, layer.in_features, dtype=torch.bfloat16, device=dev)
+            buf = layer.delta_buf if layer.sgd_lr is not None else None
+            _b.melded_bwd(dy2, layer.wq, layer.s_w, o_a, amax_oa, layer.in_features, layer.rank, dyq, s_dy, dx,
+                          layer.d_b, buf, layer.sgd_lr if layer.sgd_lr is not None else 0.0, layer._workspace(T))
+            total = dx if total is None else total.add_(dx)
+        return total.reshape(*ctx.lead, layers[0].in_features), None
+
+
+class MeldedGroup:
+    """Melded layers with a common input (q/k/v, gate/up).  `group(x)` returns one output per layer."""
+
+    def __init__(self, *layers: "MeldedLoRALinear"):
+        if not layers or any(l.in_features != layers[0].in_features for l in layers):
+            raise ValueError("a group needs layers of one input width")
+        self.layers = list(layers)
+
+    def __call__(self, x: torch.Tensor):
+        return _MeldedGroupFn.apply(x, self)
+
+
 class MeldedLoRALinear(torch.nn.Module):
     """y = x W'^T with W' the FP8 backbone that already contains the adapter; trainable only through
     the proxy buffer.  `sgd_lr` set: backward applies `DeltaBuffer += -lr dB` itself.  `sgd_lr=None`:
@@ -154,22 +221,28 @@ class LlamaBlock(torch.nn.Module):
     to put real data dependence between the projections.  `linear(in, out)` builds a projection, so
     the same block can be instantiated with another linear layer for comparison."""
 
-    def __init__(self, d_model: int, n_heads: int, d_mlp: int, linear, device="cuda"):
+    def __init__(self, d_model: int, n_heads: int, d_mlp: int, linear, device="cuda", share_quantized_inputs: bool = True):
         super().__init__()
         self.n_heads = n_heads
         self.norm1, self.norm2 = _RMSNorm(d_model, device), _RMSNorm(d_model, device)
         self.q, self.k, self.v, self.o = (linear(d_model, d_model) for _ in range(4))
         self.gate, self.up = linear(d_model, d_mlp), linear(d_model, d_mlp)
         self.down = linear(d_mlp, d_model)
+        # melded projections that share an input quantize it once
+        melded = all(isinstance(p, MeldedLoRALinear) for p in self.projections())
+        self._qkv = MeldedGroup(self.q, self.k, self.v) if melded and share_quantized_inputs else None
+        self._gate_up = MeldedGroup(self.gate, self.up) if melded and share_quantized_inputs else None
 
     def forward(self, x):                                              # x: [batch, seq, d_model] bf16
         B, S, D = x.shape
         h = self.norm1(x)
-        q, k, v = (p(h).reshape(B, S, self.n_heads, D // self.n_heads).transpose(1, 2) for p in (self.q, self.k, self.v))
+        qkv = self._qkv(h) if self._qkv is not None else (self.q(h), self.k(h), self.v(h))
+        q, k, v = (t.reshape(B, S, self.n_heads, D // self.n_heads).transpose(1, 2) for t in qkv)
         a = torch.nn.functional.scaled_dot_product_attention(q, k, v, is_causal=True)
         x = x + self.o(a.transpose(1, 2).reshape(B, S, D))
         h = self.norm2(x)
-        return x + self.down(torch.nn.functional.silu(self.gate(h)) * self.up(h))
+        gate, up = self._gate_up(h) if self._gate_up is not None else (self.gate(h), self.up(h))
+        return x + self.down(torch.nn.functional.silu(gate) * up)
 
     def projections(self):
         return [self.q, self.k, self.v, self.o, self.gate, self.up, self.down]

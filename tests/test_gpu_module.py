@@ -86,3 +86,60 @@ def test_module_initializes_itself_from_a_weight():
     off = gram - np.diag(np.diag(gram))
     assert np.max(np.abs(off)) <= 0.05 * sg[0]
     assert not lin.delta_buf.any()
+
+
+def test_group_with_one_quantized_input_equals_the_separate_layers():
+    from paper_2510_24061_amd.nn import MeldedGroup
+    T, n, r = 320, 256, 16
+    widths = (256, 128, 384)
+    g = torch.Generator().manual_seed(77)
+    x0 = torch.randn(T, n, generator=g).to(torch.bfloat16).cuda()
+    dys = [torch.randn(T, m, generator=g).to(torch.bfloat16).cuda() for m in widths]
+
+    def build():
+        layers = []
+        gg = torch.Generator().manual_seed(78)
+        for m in widths:
+            lin = MeldedLoRALinear(n, m, r, 8, sgd_lr=1e-3)
+            lin.load_weights((torch.randn(m, n, generator=gg) * 0.02).cuda(), (torch.randn(r, n, generator=gg) / r).cuda())
+            layers.append(lin)
+        return layers
+
+    sep, grp = build(), build()
+    xs = x0.clone().requires_grad_(True)
+    ys = [l(xs) for l in sep]
+    torch.autograd.backward(ys, dys)
+    xg = x0.clone().requires_grad_(True)
+    yg = MeldedGroup(*grp)(xg)
+    torch.autograd.backward(list(yg), dys)
+    torch.cuda.synchronize()
+    for a, b, ls, lg in zip(ys, yg, sep, grp):
+        assert torch.equal(a, b)                                        # same codes, same product
+        assert torch.equal(ls.d_b, lg.d_b) and torch.equal(ls.delta_buf, lg.delta_buf)
+    # input gradient: the same three bf16 terms, possibly added in another order
+    assert relf(np_of(xg.grad), np_of(xs.grad)) < 1e-2
+    # a layer whose output is not used gets a zero gradient and still takes part
+    xg2 = x0.clone().requires_grad_(True)
+    y0, _, _ = MeldedGroup(*grp)(xg2)
+    y0.backward(dys[0])
+    xs2 = x0.clone().requires_grad_(True)
+    sep[0](xs2).backward(dys[0])
+    assert torch.equal(xg2.grad, xs2.grad)
+    with pytest.raises(ValueError):
+        MeldedGroup(grp[0], MeldedLoRALinear(128, 64, 16, 4))
+
+
+def test_forward_call_accepts_an_already_quantized_input():
+    T, n, m, r, k = 200, 128, 192, 16, 4
+    d = workloads.make_inputs(T, n, m, r, seed=31)
+    wcat, s_w = oracle_weights(d["w"], d["a"])
+    a = fq.MeldedLinear(T, n, m, r, k)
+    a.wq.copy_(torch.from_numpy(wcat)); a.s_w.fill_(float(s_w))
+    a.forward(d["x"].cuda())
+    b = fq.MeldedLinear(T, n, m, r, k)
+    b.wq.copy_(a.wq); b.s_w.copy_(a.s_w)
+    b.xq.copy_(a.xq); b.s_x.copy_(a.s_x)
+    b.amax_oa.fill_(123.0)                                              # must be reset by the call
+    fq.melded_fwd(None, b.wq, b.s_w, m, r, b.xq, b.s_x, b.y, b.o_a, b.amax_oa, b.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(a.y, b.y) and torch.equal(a.o_a, b.o_a) and torch.equal(a.amax_oa, b.amax_oa)

@@ -72,7 +72,8 @@ def test_argument_validation_happens_before_any_launch(L):
         return f(_vp(a["x"]), _vp(a["wq"]), _vp(a["s_w"]), a["T"], a["n"], a["m"], a["r"], _vp(a["xq"]),
                  _vp(a["s_x"]), _vp(a["y"]), a["yt"], _vp(a["o_a"]), _vp(a["amax"]), _vp(a["ws"]), a["wsb"], None)
 
-    assert fwd(x=None) == 1 and fwd(wq=None) == 1 and fwd(amax=None) == 1
+    assert fwd(xq=None) == 1 and fwd(wq=None) == 1 and fwd(amax=None) == 1       # x alone may be NULL
+    assert fwd(x=None, xq=None) == 1 and fwd(x=odd) == 3
     assert fwd(T=0) == 2 and fwd(n=72) == 2 and fwd(m=0) == 2 and fwd(r=8) == 2 and fwd(r=512) == 2
     assert fwd(y=odd) == 3 and fwd(yt=5) == 4
     assert fwd(ws=None) == 5 and fwd(wsb=ws_bytes - 1) == 5
