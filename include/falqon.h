@@ -21,6 +21,9 @@
  *     activations as n x d columns, O = W x; T is its d.)
  *   - Every pointer is a DEVICE pointer unless it is called "host".  Scales and amax
  *     values are device scalars, so no call synchronises with the host.
+ *   - Arguments marked "in/out" are outputs of the call's own first step when its source
+ *     tensor is given and inputs when that source is NULL: xq and s_x of falqon_melded_fwd
+ *     (written by the call's quantizer when x is given; read as they are when x is NULL).
  *   - The caller owns every buffer.  The library allocates nothing and keeps no state
  *     between calls.  `ws` is caller-provided scratch of at least
  *     falqon_workspace_bytes() bytes; its contents are undefined after a call.
@@ -104,7 +107,8 @@ falqon_status falqon_quantize(const void* x, falqon_dtype xt, int64_t rows, int6
  *                 read the same activation, such as the q, k and v projections, quantize it once)
  *   wq       in   E4M3 [(m+r), n]: m backbone rows, then the r adapter rows cast with s_w
  *   s_w      in   device scalar, the backbone's scale
- *   xq, s_x  out  E4M3 [T, n] and its scale (the operands the product was formed from); in if x is NULL
+ *   xq, s_x  in/out  E4M3 [T, n] and its scale: the operands the product is formed from.  Out when
+ *                 x is given, in when x is NULL
  *   y        out  [T, m] of dtype yt
  *   o_a      out  bf16 [T, r]
  *   amax_oa  out  device scalar
@@ -129,7 +133,8 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
  *   dy         in   bf16 [T, m]
  *   o_a, amax_oa in bf16 [T, r] and device scalar, as falqon_melded_fwd produced them
  *   dyq, s_dy  out  E5M2 [T, m] and its scale
- *   dx         out  [T, n] of dtype dxt
+ *   dx         out  [T, n] of dtype dxt; NULL: the input-gradient product is skipped (a layer whose
+ *                   input needs no gradient, such as the first projections behind a frozen embedding)
  *   d_b        out  fp32 [m, r]
  *   delta_buf  i/o  nullable fp32 [m, r]
  */
@@ -200,23 +205,6 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
 falqon_status falqon_db_bf16(const uint8_t* dyq, const float* s_dy, const void* o_a,
                              int64_t T, int64_t m, int64_t r, float* d_b, float* delta_buf, float lr,
                              void* ws, size_t ws_bytes, void* stream);
-
-/*
- * Measurement aid, not a step of the method: a register-only loop of the FP8 matrix-core
- * instruction the products use (32x32x64, E4M3 x E4M3, fp32 accumulation).  Each of the
- * `workgroups` x 4 waves fills its operand registers once (lane t reads bytes [128 t, 128 t + 128)
- * of a_codes and of b_codes, so both must hold at least 8192 bytes), runs `iters` rounds of 16
- * instructions, and writes the sum of its accumulators to sink[workgroup * 256 + thread].  A launch
- * performs workgroups * 4 * iters * 16 * 2 * 32 * 32 * 64 floating-point operations with no memory
- * traffic inside the loop: timed by the caller, that is the matrix-core rate the chip sustains for
- * those operand bits, the ceiling a product kernel can be compared with besides the nominal peak.
- *
- *   a_codes, b_codes  in   E4M3 codes, device, 32-byte aligned, >= 8192 bytes each
- *   sink              out  fp32 [workgroups * 256], device
- * 1 <= workgroups <= 65536, 1 <= iters <= 1000000.
- */
-falqon_status falqon_mfma_probe(const uint8_t* a_codes, const uint8_t* b_codes, int64_t workgroups, int64_t iters,
-                                float* sink, void* stream);
 
 /*
  * Optimizer step into the proxy buffer: "DeltaBuffer <- Optimizer(dL/dB, lr)", the second line of

@@ -56,8 +56,6 @@ def lib():
         L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
         L.falqon_db_bf16.restype = c.c_int
         L.falqon_db_bf16.argtypes = [vp, f32p, vp, i64, i64, i64, vp, vp, c.c_float, vp, c.c_size_t, vp]
-        L.falqon_mfma_probe.restype = c.c_int
-        L.falqon_mfma_probe.argtypes = [vp, vp, i64, i64, vp, vp]
         L.falqon_fp8_gemm.restype = c.c_int
         L.falqon_fp8_gemm.argtypes = [vp, c.c_int, vp, c.c_int, i64, i64, i64, f32p, f32p, vp, c.c_int, vp]
         L.falqon_grad_sqnorm.restype = c.c_int
@@ -113,10 +111,20 @@ def _dev(*tensors):
 def quantize(x: torch.Tensor, fmt: int, q: torch.Tensor, scale_out: torch.Tensor,
              ws: torch.Tensor, scale_in: Optional[torch.Tensor] = None,
              amax_out: Optional[torch.Tensor] = None) -> None:
-    """falqon_quantize on a dense 2-D (or flat) tensor."""
-    _dev(x, q, scale_out, ws, scale_in, amax_out)
-    rows, cols = (x.shape if x.dim() == 2 else (1, x.numel()))
-    st = lib().falqon_quantize(_p(x), _dtype_code(x), rows, cols, cols, fmt, _p(scale_in), _p(q), cols,
+    """falqon_quantize on a 2-D (or flat) tensor.  x and q may be row-strided views (unit stride along a
+    row, any row stride that is a multiple of 16 elements): their row strides are passed as ld_x and ld_q."""
+    _dev(scale_out, ws, scale_in, amax_out)
+    if x.dim() == 2 and q.dim() == 2:
+        rows, cols = x.shape
+        if not (x.is_cuda and q.is_cuda) or q.shape != x.shape or (cols > 1 and (x.stride(1) != 1 or q.stride(1) != 1)):
+            raise ValueError("x and q must be GPU tensors of one shape with unit stride along rows")
+        ld_x = x.stride(0) if rows > 1 else cols
+        ld_q = q.stride(0) if rows > 1 else cols
+    else:
+        _dev(x, q)
+        rows, cols = 1, x.numel()
+        ld_x = ld_q = cols
+    st = lib().falqon_quantize(_p(x), _dtype_code(x), rows, cols, ld_x, fmt, _p(scale_in), _p(q), ld_q,
                                _p(scale_out), _p(amax_out), _p(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_quantize")
 
@@ -131,10 +139,11 @@ def melded_fwd(x, wq, s_w, m: int, r: int, xq, s_x, y, o_a, amax_oa, ws) -> None
 
 
 def melded_bwd(dy, wq, s_w, o_a, amax_oa, n: int, r: int, dyq, s_dy, dx, d_b, delta_buf, lr: float, ws) -> None:
+    """dx = None: the input-gradient product is skipped.  delta_buf = None: no buffer step."""
     _dev(dy, wq, s_w, o_a, amax_oa, dyq, s_dy, dx, d_b, delta_buf, ws)
     T, m = dy.shape
     st = lib().falqon_melded_bwd(_p(dy), _p(wq), _p(s_w), _p(o_a), _p(amax_oa), T, n, m, r, _p(dyq), _p(s_dy),
-                                 _p(dx), _dtype_code(dx), _p(d_b), _p(delta_buf), float(lr),
+                                 _p(dx), _dtype_code(dx) if dx is not None else BF16, _p(d_b), _p(delta_buf), float(lr),
                                  _p(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_melded_bwd")
 
@@ -168,15 +177,6 @@ def db_bf16(dyq, s_dy, o_a, d_b, delta_buf, lr: float, ws) -> None:
                               _p(delta_buf) if delta_buf is not None else None, float(lr), _p(ws),
                               ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_db_bf16")
-
-
-def mfma_probe(a_codes, b_codes, workgroups: int, iters: int, sink) -> None:
-    """Register-only FP8 matrix-core loop (measurement aid); workgroups*4*iters*16*2*32*32*64 flops per call."""
-    _dev(a_codes, b_codes, sink)
-    if a_codes.numel() < 8192 or b_codes.numel() < 8192 or sink.numel() < workgroups * 256:
-        raise ValueError("mfma_probe: operands need 8192 bytes each, sink workgroups*256 floats")
-    st = lib().falqon_mfma_probe(_p(a_codes), _p(b_codes), workgroups, iters, _p(sink), _stream())
-    _check(st, "falqon_mfma_probe")
 
 
 def grad_sqnorm(g, sum_sq, ws) -> None:

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libfalqon.so")
 SOURCES = ["falqon_api.hip", "quantize.hip", "gemm.hip", "partials.hip", "db.hip", "proxy.hip", "optimizer.hip", "init.hip",
-           "mfma_probe.hip", "db_wide.hip"]
+           "db_wide.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

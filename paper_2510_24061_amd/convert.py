@@ -78,11 +78,18 @@ class MeldedOptimizer:
 
     @torch.no_grad()
     def step(self) -> None:
+        """Layers whose backward did not run since the last step have no gradient: like a parameter
+        without `.grad` in a PyTorch optimizer they are left out of the norm and take no AdamW step
+        (their moments do not decay either).  If no layer has one, that is an error: most likely the
+        loss does not depend on the melded layers."""
+        live = [l for l in self.layers if l.backward_calls > 0]
+        if not live:
+            raise RuntimeError("no melded layer received a gradient since the last step")
         self.steps += 1
         self._sum_sq.zero_()
-        for l in self.layers:
+        for l in live:
             l.grad_sqnorm(self._sum_sq)
-        for l in self.layers:
+        for l in live:
             l.adamw_step(self.steps, self._sum_sq, self.lr, self.betas[0], self.betas[1], self.eps, self.max_norm)
         if self.steps % self.fold_every == 0:
             for l in self.layers:

@@ -173,8 +173,8 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
 {
     if (dxt != FALQON_BF16 && dxt != FALQON_F32) return FALQON_ERR_ENUM;
     if (bad_layer_shape(T, n, m, r)) return FALQON_ERR_SHAPE;
-    if (!dy || !wq || !s_w || !o_a || !amax_oa || !dyq || !s_dy || !dx || !d_b) return FALQON_ERR_NULL;
-    if (misaligned(dy) || misaligned(wq) || misaligned(o_a) || misaligned(dyq) || misaligned(dx) ||
+    if (!dy || !wq || !s_w || !o_a || !amax_oa || !dyq || !s_dy || !d_b) return FALQON_ERR_NULL;   // dx may be NULL
+    if (misaligned(dy) || misaligned(wq) || misaligned(o_a) || misaligned(dyq) || (dx && misaligned(dx)) ||
         misaligned(d_b) || (delta_buf && misaligned(delta_buf)))
         return FALQON_ERR_ALIGN;
     if ((reinterpret_cast<uintptr_t>(s_w) & 3u) || (reinterpret_cast<uintptr_t>(s_dy) & 3u) ||
@@ -203,7 +203,9 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
     // O_A, so nothing orders it against the dX product: on the large tiles both go out as one launch.
     const DbArgs d = make_db_args(dyq, o_a, amax_oa, T, m, r, reinterpret_cast<float*>(w8 + L.db_partials),
                                   db_splits(T, m));
-    if (gemm_dx_db_pair_supported(g)) {
+    if (!dx) {
+        e = launch_db_partial(d, st);                      // the layer's input needs no gradient
+    } else if (gemm_dx_db_pair_supported(g)) {
         e = launch_gemm_dx_db_pair(g, d, st);
     } else {
         e = launch_gemm(g, st);
@@ -271,18 +273,6 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
     g.c0 = c; g.ldc0 = N; g.c0_is_f32 = (ct == FALQON_F32); g.n_split = N;
     g.c1 = nullptr; g.ldc1 = 0; g.amax1 = nullptr;
     hipError_t e = launch_gemm(g, static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
-}
-
-falqon_status falqon_mfma_probe(const uint8_t* a_codes, const uint8_t* b_codes, int64_t workgroups, int64_t iters,
-                                float* sink, void* stream)
-{
-    if (workgroups < 1 || workgroups > 65536 || iters < 1 || iters > 1000000) return FALQON_ERR_SHAPE;
-    if (!a_codes || !b_codes || !sink) return FALQON_ERR_NULL;
-    if ((reinterpret_cast<uintptr_t>(a_codes) & 31u) || (reinterpret_cast<uintptr_t>(b_codes) & 31u) || misaligned(sink))
-        return FALQON_ERR_ALIGN;
-    hipError_t e = launch_mfma_probe(a_codes, b_codes, static_cast<int>(workgroups), static_cast<int>(iters), sink,
-                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 

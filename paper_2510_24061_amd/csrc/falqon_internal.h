@@ -109,8 +109,4 @@ struct AdamFactors {
 hipError_t launch_adamw_delta(const float* d_b, float* exp_avg, float* exp_avg_sq, float* delta_buf, int64_t count,
                               const AdamFactors& f, const double* sum_sq, hipStream_t stream);
 
-// mfma_probe.hip: register-only matrix-core loop (measurement aid)
-hipError_t launch_mfma_probe(const uint8_t* a_codes, const uint8_t* b_codes, int workgroups, int iters, float* sink,
-                             hipStream_t stream);
-
 }  // namespace falqon

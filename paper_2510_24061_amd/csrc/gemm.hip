@@ -24,7 +24,6 @@
 //     outputs that are never stored); the K tail is fetched from a 16-byte block of zeros.
 //   - Workgroup ids are spread round-robin over the 8 XCDs by the hardware; the id -> tile
 //     map hands each XCD a compact block of tiles so its L2 sees each operand panel once.
-#include <cstdlib>
 #include <type_traits>
 
 #include "db_tile.h"
@@ -585,16 +584,6 @@ hipError_t launch_gemm_dx_db_pair(const GemmArgs& g, const DbArgs& d, hipStream_
 hipError_t launch_gemm(const GemmArgs& g, hipStream_t stream)
 {
     if (g.M <= 0 || g.N <= 0) return hipSuccess;
-    // Tuning override (development only): FALQON_GEMM_TILE = 1 forces 256x256 tiles, 4 forces 128x128.
-    static const int forced = [] {
-        const char* e = getenv("FALQON_GEMM_TILE");
-        return e ? atoi(e) : 0;
-    }();
-    switch (forced) {
-        case 1: return launch_cfg<2, 2, 4, 4>(g, stream);   // 256x256, 4 waves
-        case 4: return launch_cfg<2, 2, 2, 2>(g, stream);   // 128x128, 4 waves
-        default: break;
-    }
     if (use_big_tiles(g.M, g.N)) return launch_cfg<2, 2, 4, 4>(g, stream);
     return launch_cfg<2, 2, 2, 2>(g, stream);
 }

@@ -1,10 +1,21 @@
 """The melded layer as a PyTorch module: autograd plumbing around the C-ABI calls.
 
-Nothing is computed here.  `MeldedLoRALinear.forward` calls `falqon_melded_fwd`, its autograd
-backward calls `falqon_melded_bwd` (which also takes the buffer step when `lr` is set), and
-`proxy_update()` / `adamw_step()` call the update entry points.  The module owns the layer's
-persistent state (concatenated FP8 weight, its scale, the proxy buffer) and a workspace; per-call
-outputs are fresh tensors so that a layer may be used several times before its backward runs.
+Nothing of the method is computed here.  `MeldedLoRALinear.forward` calls `falqon_melded_fwd`, its
+autograd backward calls `falqon_melded_bwd`, and `proxy_update()` / `adamw_step()` call the update
+entry points.  The module owns the layer's persistent state (concatenated FP8 weight, its scale, the
+proxy buffer) and a workspace; per-call outputs are fresh tensors, so a layer may be applied several
+times before its backward passes run.
+
+Where the adapter gradient goes: with an SGD rate (`sgd_lr`) every backward call takes the buffer
+step itself, so calls add up in the proxy buffer.  Without one (`sgd_lr=None`, the optimizer path)
+every backward call adds its gradient to `grad_acc` (the same call with the accumulator in the
+buffer's place and a rate of -1: `acc += -(-1) * dB`), `d_b` holds the last call's gradient, and
+`adamw_step()` consumes and clears the accumulator; `backward_calls` counts the calls since then.
+
+The layer's only differentiable state is the proxy buffer, which autograd does not see.  So that the
+backward pass runs even when the layer's input carries no gradient (the first projections behind a
+frozen embedding), every layer owns a one-element parameter that is passed through the autograd
+function as an anchor; it receives no gradient.  In that case the input-gradient product is skipped.
 """
 from typing import Optional
 
@@ -13,14 +24,34 @@ import torch
 from . import binding as _b
 
 
+def _flat_bf16(t: torch.Tensor, width: int) -> torch.Tensor:
+    t2 = t.reshape(-1, width)
+    if t2.dtype != torch.bfloat16:
+        t2 = t2.to(torch.bfloat16)
+    return t2.contiguous()
+
+
+def _layer_backward(layer: "MeldedLoRALinear", dy2: torch.Tensor, o_a, amax_oa, want_dx: bool):
+    """One falqon_melded_bwd call; returns dx (None when the input needs no gradient)."""
+    T, dev = dy2.shape[0], dy2.device
+    dyq = torch.empty(T, layer.out_features, dtype=torch.uint8, device=dev)
+    s_dy = torch.empty(1, dtype=torch.float32, device=dev)
+    dx = torch.empty(T, layer.in_features, dtype=torch.bfloat16, device=dev) if want_dx else None
+    if layer.sgd_lr is not None:
+        buf, lr = layer.delta_buf, layer.sgd_lr            # the buffer step happens inside the call
+    else:
+        buf, lr = layer.grad_acc, -1.0                      # acc += dB, waiting for adamw_step()
+    _b.melded_bwd(dy2, layer.wq, layer.s_w, o_a, amax_oa, layer.in_features, layer.rank, dyq, s_dy, dx,
+                  layer.d_b, buf, lr, layer._workspace(T))
+    layer.backward_calls += 1
+    return dx
+
+
 class _MeldedFn(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, x: torch.Tensor, layer: "MeldedLoRALinear") -> torch.Tensor:
+    def forward(ctx, x: torch.Tensor, anchor: torch.Tensor, layer: "MeldedLoRALinear") -> torch.Tensor:
         lead = x.shape[:-1]
-        x2 = x.reshape(-1, layer.in_features)
-        if x2.dtype != torch.bfloat16:
-            x2 = x2.to(torch.bfloat16)
-        x2 = x2.contiguous()
+        x2 = _flat_bf16(x, layer.in_features)
         T = x2.shape[0]
         dev = x2.device
         ws = layer._workspace(T)
@@ -36,21 +67,10 @@ class _MeldedFn(torch.autograd.Function):
 
     @staticmethod
     def backward(ctx, dy: torch.Tensor):
-        layer, T = ctx.layer, ctx.T
+        layer = ctx.layer
         o_a, amax_oa = ctx.saved_tensors
-        dy2 = dy.reshape(T, layer.out_features)
-        if dy2.dtype != torch.bfloat16:
-            dy2 = dy2.to(torch.bfloat16)
-        dy2 = dy2.contiguous()
-        dev = dy2.device
-        dyq = torch.empty(T, layer.out_features, dtype=torch.uint8, device=dev)
-        s_dy = torch.empty(1, dtype=torch.float32, device=dev)
-        dx = torch.empty(T, layer.in_features, dtype=torch.bfloat16, device=dev)
-        # with an SGD rate the buffer step happens inside the call; otherwise d_b waits for adamw_step()
-        buf = layer.delta_buf if layer.sgd_lr is not None else None
-        _b.melded_bwd(dy2, layer.wq, layer.s_w, o_a, amax_oa, layer.in_features, layer.rank, dyq, s_dy, dx,
-                      layer.d_b, buf, layer.sgd_lr if layer.sgd_lr is not None else 0.0, layer._workspace(T))
-        return dx.reshape(*ctx.lead, layer.in_features), None
+        dx = _layer_backward(layer, _flat_bf16(dy, layer.out_features), o_a, amax_oa, ctx.needs_input_grad[0])
+        return (dx.reshape(*ctx.lead, layer.in_features) if dx is not None else None), None, None
 
 
 class _MeldedGroupFn(torch.autograd.Function):
@@ -58,14 +78,11 @@ class _MeldedGroupFn(torch.autograd.Function):
     product runs on those codes, and the input gradients are added."""
 
     @staticmethod
-    def forward(ctx, x: torch.Tensor, group: "MeldedGroup"):
+    def forward(ctx, x: torch.Tensor, anchor: torch.Tensor, group: "MeldedGroup"):
         layers = group.layers
         first = layers[0]
         lead = x.shape[:-1]
-        x2 = x.reshape(-1, first.in_features)
-        if x2.dtype != torch.bfloat16:
-            x2 = x2.to(torch.bfloat16)
-        x2 = x2.contiguous()
+        x2 = _flat_bf16(x, first.in_features)
         T, dev = x2.shape[0], x2.device
         xq = torch.empty(T, first.in_features, dtype=torch.uint8, device=dev)
         s_x = torch.empty(1, dtype=torch.float32, device=dev)
@@ -87,25 +104,18 @@ class _MeldedGroupFn(torch.autograd.Function):
     def backward(ctx, *dys):
         layers, T = ctx.group.layers, ctx.T
         saved = ctx.saved_tensors
+        want_dx = ctx.needs_input_grad[0]
         total = None
         for i, (layer, dy) in enumerate(zip(layers, dys)):
             o_a, amax_oa = saved[2 * i], saved[2 * i + 1]
-            dev = o_a.device
             if dy is None:
-                dy2 = torch.zeros(T, layer.out_features, dtype=torch.bfloat16, device=dev)
+                dy2 = torch.zeros(T, layer.out_features, dtype=torch.bfloat16, device=o_a.device)
             else:
-                dy2 = dy.reshape(T, layer.out_features)
-                if dy2.dtype != torch.bfloat16:
-                    dy2 = dy2.to(torch.bfloat16)
-                dy2 = dy2.contiguous()
-            dyq = torch.empty(T, layer.out_features, dtype=torch.uint8, device=dev)
-            s_dy = torch.empty(1, dtype=torch.float32, device=dev)
-            dx = torch.empty(T, layer.in_features, dtype=torch.bfloat16, device=dev)
-            buf = layer.delta_buf if layer.sgd_lr is not None else None
-            _b.melded_bwd(dy2, layer.wq, layer.s_w, o_a, amax_oa, layer.in_features, layer.rank, dyq, s_dy, dx,
-                          layer.d_b, buf, layer.sgd_lr if layer.sgd_lr is not None else 0.0, layer._workspace(T))
-            total = dx if total is None else total.add_(dx)
-        return total.reshape(*ctx.lead, layers[0].in_features), None
+                dy2 = _flat_bf16(dy, layer.out_features)
+            dx = _layer_backward(layer, dy2, o_a, amax_oa, want_dx)
+            if want_dx:
+                total = dx if total is None else total.add_(dx)
+        return (total.reshape(*ctx.lead, layers[0].in_features) if want_dx else None), None, None
 
 
 class MeldedGroup:
@@ -117,13 +127,13 @@ class MeldedGroup:
         self.layers = list(layers)
 
     def __call__(self, x: torch.Tensor):
-        return _MeldedGroupFn.apply(x, self)
+        return _MeldedGroupFn.apply(x, self.layers[0]._anchor, self)
 
 
 class MeldedLoRALinear(torch.nn.Module):
     """y = x W'^T with W' the FP8 backbone that already contains the adapter; trainable only through
     the proxy buffer.  `sgd_lr` set: backward applies `DeltaBuffer += -lr dB` itself.  `sgd_lr=None`:
-    backward leaves dB in `d_b`; call `adamw_step()` (after `grad_sqnorm()` over all layers if the
+    backward adds dB to `grad_acc`; call `adamw_step()` (after `grad_sqnorm()` over all layers if the
     gradient norm is clipped), then `proxy_update()` at the chosen cadence."""
 
     def __init__(self, in_features: int, out_features: int, rank: int, top_k: int, sgd_lr: Optional[float] = 2e-4,
@@ -135,20 +145,25 @@ class MeldedLoRALinear(torch.nn.Module):
         self.register_buffer("wq", torch.zeros(out_features + rank, in_features, dtype=torch.uint8, device=dev))
         self.register_buffer("s_w", torch.ones(1, dtype=torch.float32, device=dev))
         self.register_buffer("delta_buf", torch.zeros(out_features, rank, dtype=torch.float32, device=dev))
-        self.d_b = torch.zeros(out_features, rank, dtype=torch.float32, device=dev)
+        self.d_b = torch.zeros(out_features, rank, dtype=torch.float32, device=dev)       # the last backward call's dB
+        self.grad_acc = (torch.zeros(out_features, rank, dtype=torch.float32, device=dev)
+                         if sgd_lr is None else None)                                         # sum of dB since adamw_step()
+        self.backward_calls = 0
         self.idx = torch.zeros(top_k, dtype=torch.int32, device=dev)
         self.exp_avg = None
         self.exp_avg_sq = None
         self._ws = None
-        self._ws_tokens = 0
+        # keeps autograd's backward running when the input carries no gradient; never receives one itself
+        self._anchor = torch.nn.Parameter(torch.zeros(1, dtype=torch.float32, device=dev))
 
     def _workspace(self, T: int) -> torch.Tensor:
-        if self._ws is None or T > self._ws_tokens:
-            nbytes = _b.workspace_bytes(T, self.in_features, self.out_features, self.rank)
-            if nbytes == 0:
-                raise ValueError("invalid layer shape")
+        """A workspace of at least the bytes this token count needs (the size is not monotonic in T,
+        so it is asked for on every call and the buffer only ever grows)."""
+        nbytes = _b.workspace_bytes(T, self.in_features, self.out_features, self.rank)
+        if nbytes == 0:
+            raise ValueError("invalid layer shape")
+        if self._ws is None or self._ws.numel() < nbytes:
             self._ws = torch.empty(nbytes, dtype=torch.uint8, device=self.wq.device)
-            self._ws_tokens = T
         return self._ws
 
     @torch.no_grad()
@@ -183,20 +198,31 @@ class MeldedLoRALinear(torch.nn.Module):
         return sigma
 
     def forward(self, x: torch.Tensor) -> torch.Tensor:
-        return _MeldedFn.apply(x, self)
+        return _MeldedFn.apply(x, self._anchor, self)
+
+    def _accumulated(self) -> torch.Tensor:
+        if self.grad_acc is None:
+            raise RuntimeError("this layer takes its buffer step inside backward (sgd_lr is set); "
+                               "build it with sgd_lr=None for the optimizer path")
+        return self.grad_acc
 
     @torch.no_grad()
     def grad_sqnorm(self, sum_sq: torch.Tensor) -> None:
-        _b.grad_sqnorm(self.d_b, sum_sq, self._workspace(16))
+        """*sum_sq += squared norm of the gradient accumulated since the last adamw_step()."""
+        _b.grad_sqnorm(self._accumulated(), sum_sq, self._workspace(16))
 
     @torch.no_grad()
     def adamw_step(self, step: int, sum_sq: Optional[torch.Tensor] = None, lr: float = 2e-4, beta1: float = 0.9,
                    beta2: float = 0.999, eps: float = 1e-8, max_norm: float = 0.3) -> None:
+        """AdamW on the accumulated gradient into the proxy buffer; clears the accumulator."""
+        g = self._accumulated()
         if self.exp_avg is None:
-            self.exp_avg = torch.zeros_like(self.d_b)
-            self.exp_avg_sq = torch.zeros_like(self.d_b)
-        _b.adamw_delta(self.d_b, self.exp_avg, self.exp_avg_sq, self.delta_buf, step, lr, beta1, beta2, eps, sum_sq,
+            self.exp_avg = torch.zeros_like(g)
+            self.exp_avg_sq = torch.zeros_like(g)
+        _b.adamw_delta(g, self.exp_avg, self.exp_avg_sq, self.delta_buf, step, lr, beta1, beta2, eps, sum_sq,
                        max_norm)
+        g.zero_()
+        self.backward_calls = 0
 
     @torch.no_grad()
     def proxy_update(self, clear_selected: bool = True) -> torch.Tensor:

@@ -30,13 +30,14 @@ def test_melded_model_matches_the_original_closely_and_learns():
     with torch.no_grad():
         assert float(model(input_ids=ids, labels=ids).loss) == pytest.approx(loss_before, abs=0.1)
     opt = MeldedOptimizer(layers, lr=3e-3, max_norm=1.0)
-    emb = model.get_input_embeddings()
     wq0 = [l.wq.clone() for l in layers]
     losses = []
     for _ in range(40):
-        h = emb(ids).detach().requires_grad_(True)        # the melded layers need an input that carries a gradient
-        loss = model(inputs_embeds=h, labels=ids).loss
+        # called the ordinary way: the embedding and the norms are frozen, so the first block's q, k and v
+        # projections see an input without a gradient and must still form theirs
+        loss = model(input_ids=ids, labels=ids).loss
         loss.backward()
+        assert all(l.backward_calls == 1 for l in layers)
         opt.step()
         losses.append(float(loss.detach()))
     print("loss every 5 steps:", [round(v, 3) for v in losses[::5]], flush=True)

@@ -104,6 +104,44 @@ def test_forward_exact_integer_case_is_bit_exact(T, n, m, r):
     assert np.array_equal(np_of(layer.o_a).astype(np.float64), oracle.round_bf16(want[:, m:]).astype(np.float64))
 
 
+@pytest.mark.parametrize("T,n,m,r", [(2400, 3328, 3584, 64),     # whole tiles, adapter columns beside them
+                                     (2400, 3344, 3568, 64),     # ragged token, column and K tails
+                                     (2304, 1024, 3600, 64)])    # adapter columns inside the last tile column
+def test_large_tile_paths_exact_integer_case_is_bit_exact(T, n, m, r):
+    """The exact-integer case at sizes that take the launches the benchmark times (256x256 backbone
+    tiles together with the adapter's products): forward and backward, fp32 outputs bit for bit."""
+    g = np.random.default_rng(3)
+    xi = g.integers(-4, 5, size=(T, n)).astype(np.float32)
+    xi[5, 7] = 7.0                                   # s_x = 64
+    wi = g.integers(-8, 9, size=(m + r, n)).astype(np.float32)
+    wcat = oracle.fp8_encode(wi, oracle.E4M3)
+    layer = layer_on_gpu(T, n, m, r, 4, wcat, np.float32(2.0), torch.float32)
+    print(f"exact forward T={T} n={n} m={m}", flush=True)
+    layer.forward(torch.from_numpy(xi).to(torch.bfloat16).cuda())
+    torch.cuda.synchronize()
+    assert layer.s_x.item() == 64.0
+    want = (xi.astype(np.float64) @ wi.astype(np.float64).T) / 2.0
+    assert np.max(np.abs(want)) * 128.0 < 2.0 ** 24               # every partial sum is an exact fp32 integer
+    assert np.array_equal(np_of(layer.y).astype(np.float64), want[:, :m])
+    o_a_want = oracle.round_bf16(want[:, m:])
+    assert np.array_equal(np_of(layer.o_a), o_a_want)
+    assert layer.amax_oa.item() == np.max(np.abs(o_a_want))
+    gi = g.integers(-3, 4, size=(T, m)).astype(np.float32)
+    gi[3, 11] = 7.0                                  # s_dy = 8192
+    oa = g.integers(-3, 4, size=(T, r)).astype(np.float32)
+    oa[9, 2] = 7.0                                   # s_oa = 64
+    layer.o_a.copy_(torch.from_numpy(oa).to(torch.bfloat16))
+    layer.amax_oa.fill_(7.0)
+    print(f"exact backward T={T} n={n} m={m}", flush=True)
+    layer.backward(torch.from_numpy(gi).to(torch.bfloat16).cuda(), accumulate=False)
+    torch.cuda.synchronize()
+    assert layer.s_dy.item() == 8192.0
+    dx_want = (gi.astype(np.float64) @ wi[:m].astype(np.float64)) / 2.0
+    assert np.max(np.abs(dx_want)) * 2.0 < 2.0 ** 24
+    assert np.array_equal(np_of(layer.dx).astype(np.float64), dx_want)
+    assert np.array_equal(np_of(layer.d_b).astype(np.float64), gi.astype(np.float64).T @ oa.astype(np.float64))
+
+
 def _check_backward(T, n, m, r, k, d, wcat, s_w, out_dtype, n_sample=96):
     x = d["x"].float().numpy()
     # O_A and its maximum come from the oracle's forward (all rows, adapter columns only)
@@ -334,3 +372,90 @@ def test_random_shapes_forward_backward_update(shape):
     idx_ref, w_ref, buf_ref = oracle.proxy_update(buf.numpy(), wcat, m, r, k)
     assert np.array_equal(np_of(layer.idx), idx_ref) and np.array_equal(np_of(layer.wq), w_ref)
     assert np_of(layer.delta_buf).tobytes() == buf_ref.tobytes()
+
+
+def _guarded(shape, dtype, fill):
+    """A dense tensor placed in the middle of a larger allocation whose other bytes hold `fill`."""
+    numel = int(np.prod(shape))
+    es = torch.empty(0, dtype=dtype).element_size()
+    guard = 4096 // es
+    whole = torch.empty(numel + 2 * guard, dtype=dtype, device="cuda")
+    whole.view(torch.uint8).fill_(fill)
+    return whole, whole[guard: guard + numel].view(*shape), guard
+
+
+def _guards_intact(whole, guard, fill):
+    raw = whole.view(torch.uint8)
+    es = whole.element_size()
+    return bool((raw[: guard * es] == fill).all().item()) and bool((raw[-guard * es:] == fill).all().item())
+
+
+@pytest.mark.parametrize("shape", [(200, 384, 208, 16), (300, 1024, 1040, 64), (520, 272, 528, 32), (100, 336, 384, 48),
+                                   (2100, 1024, 4112, 48), (2400, 3408, 3328, 32), (2305, 2064, 3600, 64)])
+@pytest.mark.parametrize("out_dtype", [torch.float32, torch.bfloat16])
+def test_outputs_stay_inside_their_buffers(shape, out_dtype):
+    """Ragged shapes: every output sits between guard bands, which must keep their bytes (the tile
+    code clamps out-of-range rows and columns to valid ones and must never store them)."""
+    T, n, m, r = shape
+    fill = 0x5A
+    d, wcat, s_w = _inputs(T, n, m, r, True, seed=900 + T)
+    u8, f32, bf16 = torch.uint8, torch.float32, torch.bfloat16
+    bufs = {"xq": _guarded((T, n), u8, fill), "y": _guarded((T, m), out_dtype, fill), "o_a": _guarded((T, r), bf16, fill),
+            "dyq": _guarded((T, m), u8, fill), "dx": _guarded((T, n), out_dtype, fill), "d_b": _guarded((m, r), f32, fill),
+            "delta": _guarded((m, r), f32, fill), "wq": _guarded((m + r, n), u8, fill), "idx": _guarded((8,), torch.int32, fill)}
+    t = {k: v[1] for k, v in bufs.items()}
+    t["wq"].copy_(torch.from_numpy(wcat))
+    t["delta"].zero_()
+    s_wt = torch.full((1,), float(s_w), device="cuda")
+    s_x, s_dy, amax_oa = (torch.zeros(1, device="cuda") for _ in range(3))
+    ws = torch.empty(fq.workspace_bytes(T, n, m, r), dtype=u8, device="cuda")
+    print(f"guards T={T} n={n} m={m} r={r} {out_dtype}", flush=True)
+    fq.melded_fwd(d["x"].cuda(), t["wq"], s_wt, m, r, t["xq"], s_x, t["y"], t["o_a"], amax_oa, ws)
+    fq.melded_bwd(d["dy"].cuda(), t["wq"], s_wt, t["o_a"], amax_oa, n, r, t["dyq"], s_dy, t["dx"], t["d_b"], t["delta"], 0.5, ws)
+    fq.proxy_update(t["delta"], t["wq"], m, r, 8, t["idx"], ws)
+    torch.cuda.synchronize()
+    for name, (whole, _, guard) in bufs.items():
+        assert _guards_intact(whole, guard, fill), name
+    # and the outputs are the ones an unguarded layer produces
+    layer = layer_on_gpu(T, n, m, r, 8, wcat, s_w, out_dtype)
+    layer.forward(d["x"].cuda()); layer.backward(d["dy"].cuda(), lr=0.5); layer.update()
+    torch.cuda.synchronize()
+    for name, other in (("xq", layer.xq), ("y", layer.y), ("o_a", layer.o_a), ("dyq", layer.dyq), ("dx", layer.dx),
+                        ("d_b", layer.d_b), ("delta", layer.delta_buf), ("wq", layer.wq), ("idx", layer.idx)):
+        assert torch.equal(t[name], other), name
+
+
+@pytest.mark.parametrize("shapes", [((300, 512, 528, 32, 16), (300, 528, 272, 32, 8))])
+def test_accumulate_over_four_steps_then_one_update(shapes):
+    """The cadence of the 224-layer configuration on two small layers: four forward/backward steps
+    add into each layer's buffer (nothing is folded in between), then every layer is updated once.
+    After each step the buffer must equal the oracle's step applied to the gradient the call
+    returned, bit for bit; the gradients themselves stay within tolerance of the oracle's; the
+    update's indices and weight bytes must be the oracle's on that buffer."""
+    lr = 2e-4
+    layers, states = [], []
+    for (T, n, m, r, k) in shapes:
+        d, wcat, s_w = _inputs(T, n, m, r, True, seed=5000 + n)
+        layers.append((layer_on_gpu(T, n, m, r, k, wcat, s_w, torch.bfloat16), (T, n, m, r, k), wcat, s_w))
+        states.append(np.zeros((m, r), np.float32))
+    for step in range(4):
+        for li, (layer, (T, n, m, r, k), wcat, s_w) in enumerate(layers):
+            d = workloads.make_inputs(T, n, m, r, 6000 + 10 * step + li, True)
+            layer.forward(d["x"].cuda())
+            layer.backward(d["dy"].cuda(), lr=lr)
+            torch.cuda.synchronize()
+            f = oracle.layer_fwd(d["x"].float().numpy(), wcat, s_w, m, r)
+            assert np.array_equal(np_of(layer.xq), f["xq"])
+            b = oracle.layer_bwd(d["dy"].float().numpy(), wcat, s_w, np_of(layer.o_a), np.float32(layer.amax_oa.item()), m, r)
+            assert np.array_equal(np_of(layer.dyq), b["dyq"])
+            assert relf(np_of(layer.d_b), b["db"]) < TOL
+            states[li] = oracle.delta_accumulate(states[li], np_of(layer.d_b).astype(np.float64), np.float32(lr))
+            assert np_of(layer.delta_buf).tobytes() == states[li].tobytes(), (step, li)
+            assert np.array_equal(np_of(layer.wq), wcat)               # nothing is folded before the update
+    for li, (layer, (T, n, m, r, k), wcat, s_w) in enumerate(layers):
+        layer.update()
+        torch.cuda.synchronize()
+        idx_ref, w_ref, buf_ref = oracle.proxy_update(states[li], wcat, m, r, k)
+        assert np.array_equal(np_of(layer.idx), idx_ref)
+        assert np.array_equal(np_of(layer.wq), w_ref)
+        assert np_of(layer.delta_buf).tobytes() == buf_ref.tobytes()

@@ -143,3 +143,82 @@ def test_forward_call_accepts_an_already_quantized_input():
     fq.melded_fwd(None, b.wq, b.s_w, m, r, b.xq, b.s_x, b.y, b.o_a, b.amax_oa, b.ws)
     torch.cuda.synchronize()
     assert torch.equal(a.y, b.y) and torch.equal(a.o_a, b.o_a) and torch.equal(a.amax_oa, b.amax_oa)
+
+
+def test_workspace_follows_the_bytes_needed_not_the_token_count():
+    """The workspace size is not monotonic in T (the adapter product's split count drops when T
+    grows past a tile boundary): a layer that has seen 4200 tokens must still serve 4096."""
+    n = m = 4096
+    r = 64
+    assert fq.workspace_bytes(4096, n, m, r) > fq.workspace_bytes(4200, n, m, r)
+    g = torch.Generator().manual_seed(12)
+    lin = MeldedLoRALinear(n, m, r, 8, sgd_lr=1e-3)
+    lin.load_weights((torch.randn(m, n, generator=g) * 0.02).cuda(), (torch.randn(r, n, generator=g) / r).cuda())
+    for T in (4200, 4096, 16, 4200):
+        x = torch.randn(T, n, generator=g).to(torch.bfloat16).cuda().requires_grad_(True)
+        y = lin(x)
+        y.backward(torch.ones_like(y))
+        torch.cuda.synchronize()
+        assert torch.isfinite(x.grad.float()).all()
+    lin.proxy_update()
+    torch.cuda.synchronize()
+
+
+def test_backward_runs_when_the_input_carries_no_gradient():
+    """A layer behind frozen modules: its input does not require a gradient, its adapter gradient must
+    still be formed (and be the one a call with an input gradient forms)."""
+    T, n, m, r, k = 192, 256, 384, 32, 6
+    d = workloads.make_inputs(T, n, m, r, seed=616)
+    dy = d["dy"].cuda()
+    a = MeldedLoRALinear(n, m, r, k, sgd_lr=None)
+    a.load_weights(d["w"].cuda(), d["a"].cuda())
+    b = MeldedLoRALinear(n, m, r, k, sgd_lr=None)
+    b.load_weights(d["w"].cuda(), d["a"].cuda())
+    x_frozen = d["x"].cuda()
+    assert not x_frozen.requires_grad
+    ya = a(x_frozen)
+    assert ya.requires_grad
+    ya.backward(dy)
+    xb = d["x"].cuda().requires_grad_(True)
+    b(xb).backward(dy)
+    torch.cuda.synchronize()
+    assert a.backward_calls == 1 and a._anchor.grad is None
+    assert a.d_b.abs().sum() > 0
+    assert torch.equal(a.d_b, b.d_b) and torch.equal(a.grad_acc, b.grad_acc)
+    assert xb.grad is not None
+
+
+def test_gradients_of_several_backward_calls_add_up():
+    """Optimizer path: a layer applied twice in one graph, then a second micro-batch, before one
+    optimizer step.  The accumulator holds the sum of the three gradients; the step clears it."""
+    T, n, m, r, k = 128, 256, 272, 16, 6
+    d = workloads.make_inputs(T, n, m, r, seed=617)
+    lin = MeldedLoRALinear(n, m, r, k, sgd_lr=None)
+    lin.load_weights(d["w"].cuda(), d["a"].cuda())
+    x1 = d["x"].cuda().requires_grad_(True)
+    x2 = (d["x"].cuda().float() * 0.5).to(torch.bfloat16).requires_grad_(True)
+    dy = d["dy"].cuda()
+    singles = []
+    for x, g in ((x2, dy * 2), (x1, dy), (x1, dy * 3)):              # autograd runs the later use first
+        ref = MeldedLoRALinear(n, m, r, k, sgd_lr=None)
+        ref.wq.copy_(lin.wq); ref.s_w.copy_(lin.s_w)
+        ref(x.detach()).backward(g)
+        singles.append(ref.d_b.clone())
+    y = lin(x1) + 2.0 * lin(x2)                                        # one graph, two uses
+    y.backward(dy)
+    lin(x1).backward(dy * 3)                                           # a second micro-batch
+    torch.cuda.synchronize()
+    assert lin.backward_calls == 3
+    want = (singles[0] + singles[1]) + singles[2]
+    alt = (singles[1] + singles[0]) + singles[2]
+    assert torch.equal(lin.grad_acc, want) or torch.equal(lin.grad_acc, alt)
+    ss = torch.zeros(1, dtype=torch.float64, device="cuda")
+    lin.grad_sqnorm(ss)
+    lin.adamw_step(1, ss)
+    torch.cuda.synchronize()
+    assert lin.backward_calls == 0 and not lin.grad_acc.any()
+    assert lin.delta_buf.abs().sum() > 0
+    ref_buf = oracle.adamw_delta(np_of(want), np.zeros((m, r), np.float32), np.zeros((m, r), np.float32),
+                                 np.zeros((m, r), np.float32), 1,
+                                 clip_coef=oracle.clip_coef(oracle.sum_squares(np_of(want)), 0.3))[2]
+    assert relf(np_of(lin.delta_buf), ref_buf) < 1e-5

@@ -133,3 +133,30 @@ def test_quantize_more_than_2_to_31_elements():
     for lo, hi in ((0, 256), (boundary - 128, boundary + 128), (rows - 256, rows)):
         ref, _, _ = oracle.quantize(x[lo:hi].float().numpy(), oracle.E4M3, scale_in=s_ref)
         assert np.array_equal(np_of(q[lo:hi]), ref), (lo, hi)
+
+
+@pytest.mark.parametrize("fmt", [fq.E4M3, fq.E5M2])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("rows,cols,pad_x,pad_q", [(37, 48, 16, 32), (300, 1024, 48, 0), (129, 272, 0, 16),
+                                                   (2050, 4096, 32, 64)])
+def test_quantize_row_strided_input_and_output(fmt, dtype, rows, cols, pad_x, pad_q):
+    """Row strides larger than the row length (ld_x > cols, ld_q > cols): the padding elements of x,
+    which here hold values far above the tensor's own maximum, must not enter the scale, and the
+    padding bytes of q must stay as they were."""
+    g = torch.Generator().manual_seed(rows + cols)
+    big = torch.full((rows, cols + pad_x), 1.0e6).to(dtype)
+    big[:, :cols] = (torch.randn(rows, cols, generator=g) * torch.exp(torch.randn(rows, 1, generator=g))).to(dtype)
+    xg = big.cuda()[:, :cols]
+    qbig = torch.full((rows, cols + pad_q), 0xAA, dtype=torch.uint8, device="cuda")
+    q = qbig[:, :cols]
+    s = torch.zeros(1, device="cuda")
+    amax = torch.zeros(1, device="cuda")
+    ws = torch.empty(8192, dtype=torch.uint8, device="cuda")
+    fq.quantize(xg, fmt, q, s, ws, amax_out=amax)
+    torch.cuda.synchronize()
+    q_ref, s_ref, amax_ref = oracle.quantize(big[:, :cols].float().numpy(), fmt)
+    assert np.float32(s.item()).tobytes() == s_ref.tobytes()
+    assert np.float32(amax.item()).tobytes() == amax_ref.tobytes()
+    got = np_of(qbig)
+    assert np.array_equal(got[:, :cols], q_ref)
+    assert np.all(got[:, cols:] == 0xAA)

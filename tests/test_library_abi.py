@@ -160,19 +160,6 @@ def test_initialization_argument_validation(L):
     assert f(a=odd) == 3 and f(ws=None) == 5 and f(wb=wsb - 1) == 5
 
 
-def test_mfma_probe_argument_validation(L):
-    p = L.falqon_mfma_probe
-    ok, odd = 0x10000, 0x10010                                      # 32-byte aligned / only 16-byte aligned
-    assert p(None, _vp(ok), 1, 1, _vp(ok), None) == 1
-    assert p(_vp(ok), _vp(ok), 1, 1, None, None) == 1
-    assert p(_vp(ok), _vp(ok), 0, 1, _vp(ok), None) == 2
-    assert p(_vp(ok), _vp(ok), 65537, 1, _vp(ok), None) == 2
-    assert p(_vp(ok), _vp(ok), 1, 0, _vp(ok), None) == 2
-    assert p(_vp(ok), _vp(ok), 1, 1000001, _vp(ok), None) == 2
-    assert p(_vp(odd), _vp(ok), 1, 1, _vp(ok), None) == 3
-    assert p(_vp(ok), _vp(odd), 1, 1, _vp(ok), None) == 3
-
-
 def test_db_bf16_argument_validation(L):
     f = L.falqon_db_bf16
     ok, odd = 0x10000, 0x10004
