@@ -56,7 +56,8 @@ typedef enum {
     FALQON_ERR_ALIGN = 3,      /* a pointer is not 16-byte aligned */
     FALQON_ERR_ENUM = 4,       /* unknown format or dtype */
     FALQON_ERR_WORKSPACE = 5,  /* ws is NULL or smaller than falqon_workspace_bytes() */
-    FALQON_ERR_HIP = 6         /* a HIP launch failed */
+    FALQON_ERR_HIP = 6,        /* a HIP launch failed */
+    FALQON_ERR_LIMIT = 7       /* a size exceeds the fixed scratch of an entry point that takes no workspace */
 } falqon_status;
 
 typedef enum { FALQON_E4M3 = 0, FALQON_E5M2 = 1 } falqon_fmt;
@@ -166,6 +167,23 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
 falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
                                   int32_t* idx_out, int clear_selected,
                                   void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * falqon_proxy_update for callers that cannot allocate device memory and so have no workspace to
+ * pass: code under HIP graph capture, tight loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels and bit-identical results; the scratch (row scores and the staged rows
+ * of the selection) lives in a static device array of the library, 384 KiB per GPU, held until the
+ * process ends.  The call allocates and frees nothing.
+ *
+ * Limits: m <= 16384 and k * r <= 65536, else FALQON_ERR_LIMIT and nothing is launched.
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two
+ * streams, two threads) race; order them.  The first call on a device looks up the array's
+ * address (once per device, kept for the life of the process, guarded by a mutex); make that call
+ * outside a graph capture.  Nothing in the array needs clearing between calls: each call writes
+ * every score and every staged row it later reads.
+ */
+falqon_status falqon_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
+                                         int32_t* idx_out, int clear_selected, void* stream);
 
 /*
  * Building block: one FP8 product with rescale, C = A . op(B) / (s_a * s_b), fp32 accumulation.

@@ -54,6 +54,8 @@ def lib():
                                         f32p, f32p, c.c_float, vp, c.c_size_t, vp]
         L.falqon_proxy_update.restype = c.c_int
         L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
+        L.falqon_proxy_update_static.restype = c.c_int
+        L.falqon_proxy_update_static.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp]
         L.falqon_db_bf16.restype = c.c_int
         L.falqon_db_bf16.argtypes = [vp, f32p, vp, i64, i64, i64, vp, vp, c.c_float, vp, c.c_size_t, vp]
         L.falqon_fp8_gemm.restype = c.c_int
@@ -154,6 +156,15 @@ def proxy_update(delta_buf, wq, m: int, r: int, k: int, idx_out, ws, clear_selec
     st = lib().falqon_proxy_update(_p(delta_buf), _p(wq), n, m, r, k, _p(idx_out), 1 if clear_selected else 0,
                                    _p(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_proxy_update")
+
+
+def proxy_update_static(delta_buf, wq, m: int, r: int, k: int, idx_out, clear_selected: bool = True) -> None:
+    """falqon_proxy_update on the library's static device scratch: no workspace, nothing allocated."""
+    _dev(delta_buf, wq, idx_out)
+    n = wq.shape[1]
+    st = lib().falqon_proxy_update_static(_p(delta_buf), _p(wq), n, m, r, k, _p(idx_out), 1 if clear_selected else 0,
+                                          _stream())
+    _check(st, "falqon_proxy_update_static")
 
 
 def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c) -> None:

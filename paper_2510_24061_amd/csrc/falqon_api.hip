@@ -57,6 +57,7 @@ const char* falqon_status_string(falqon_status s)
         case FALQON_ERR_ENUM: return "unknown format or dtype";
         case FALQON_ERR_WORKSPACE: return "workspace missing or too small";
         case FALQON_ERR_HIP: return "HIP launch failed";
+        case FALQON_ERR_LIMIT: return "size beyond the limit of the library's static scratch";
     }
     return "unknown status";
 }
@@ -251,6 +252,19 @@ falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int6
     hipError_t e = launch_proxy_update(delta_buf, wq, n, m, r, k, idx_out, clear_selected,
                                        reinterpret_cast<double*>(w8 + L.scores),
                                        reinterpret_cast<float*>(w8 + L.delta_sel), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
+falqon_status falqon_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
+                                         int32_t* idx_out, int clear_selected, void* stream)
+{
+    if (bad_layer_shape(1, n, m, r) || m > 65536 || k < 1 || k > m) return FALQON_ERR_SHAPE;
+    if (m > kStaticMaxRows || k * r > kStaticMaxSelected) return FALQON_ERR_LIMIT;
+    if (!delta_buf || !wq || !idx_out) return FALQON_ERR_NULL;
+    if (misaligned(delta_buf) || misaligned(wq) || (reinterpret_cast<uintptr_t>(idx_out) & 3u))
+        return FALQON_ERR_ALIGN;
+    hipError_t e = launch_proxy_update_static(delta_buf, wq, n, m, r, k, idx_out, clear_selected,
+                                              static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 

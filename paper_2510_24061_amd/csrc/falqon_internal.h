@@ -89,6 +89,12 @@ hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t
                                int32_t* idx_out, int clear_selected, double* scores, float* delta_sel,
                                hipStream_t stream);
 
+// The same update on the library's own static device scratch (no workspace, no allocation).
+constexpr int64_t kStaticMaxRows = 16384;          // m
+constexpr int64_t kStaticMaxSelected = 65536;      // k * r
+hipError_t launch_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
+                                      int32_t* idx_out, int clear_selected, hipStream_t stream);
+
 // ---- initialization (init.hip) -----------------------------------------------------------------
 hipError_t launch_init_residual(const float* w, const uint8_t* wq, const float* s_w, int64_t count, float* e,
                                 hipStream_t stream);

@@ -14,6 +14,8 @@
 //   3. requantize: value(W~[i,j]) + sum_p delta[p] * value(A~[p,j]) in fp64 (p ascending),
 //      rounded to fp32, cast to E4M3, written back.  A~ is rows [m, m+r) of the concatenated
 //      weight, in the same scaled domain as W~, so the backbone's scale never enters.
+#include <mutex>
+
 #include "falqon_internal.h"
 
 namespace falqon {
@@ -21,6 +23,13 @@ namespace {
 
 constexpr int kThreads = 256;
 constexpr int kScoreRows = 64;
+
+// Scratch of the entry point that may not allocate and takes no workspace: row scores for up to
+// kStaticMaxRows rows, then the staged buffer rows of the selection (k * r floats).  One copy per GPU,
+// held until the process ends; every call on a GPU uses it, so calls that overlap on one GPU race.
+constexpr size_t kStaticScoreBytes = sizeof(double) * kStaticMaxRows;
+constexpr size_t kStaticBytes = kStaticScoreBytes + sizeof(float) * kStaticMaxSelected;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
 
 // grid: ceil(m / 64); dynamic LDS: 64 * (r + 4) floats
 __global__ void __launch_bounds__(kThreads)
@@ -189,6 +198,39 @@ row_requantize_kernel(uint8_t* wq, int64_t n, int64_t m, int64_t r, const int32_
 }
 
 }  // namespace
+
+// Device address of `scratch` on the current GPU.  In host code the array's name is only a handle:
+// the address is looked up once per device and kept; every launch below receives that pointer.
+static hipError_t static_scratch(unsigned char** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static unsigned char* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptrs[dev] = static_cast<unsigned char*>(p);
+    }
+    *out = ptrs[dev];
+    return hipSuccess;
+}
+
+hipError_t launch_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
+                                      int32_t* idx_out, int clear_selected, hipStream_t stream)
+{
+    unsigned char* base = nullptr;
+    hipError_t e = static_scratch(&base);
+    if (e != hipSuccess) return e;
+    return launch_proxy_update(delta_buf, wq, n, m, r, k, idx_out, clear_selected, reinterpret_cast<double*>(base),
+                               reinterpret_cast<float*>(base + kStaticScoreBytes), stream);
+}
 
 hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
                                int32_t* idx_out, int clear_selected, double* scores, float* delta_sel,

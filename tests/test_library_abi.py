@@ -31,7 +31,7 @@ def test_exports_every_declared_symbol(L):
 def test_status_strings(L):
     import paper_2510_24061_amd as fq
     assert fq.status_string(0) == "ok"
-    assert len({fq.status_string(i) for i in range(7)}) == 7
+    assert len({fq.status_string(i) for i in range(8)}) == 8
 
 
 def test_workspace_bytes(L):
@@ -175,3 +175,15 @@ def test_db_bf16_argument_validation(L):
     assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), _vp(odd), lr, _vp(ok), big, None) == 3
     assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), None, lr, None, big, None) == 5
     assert f(_vp(ok), _vp(ok), _vp(ok), 64, 64, 16, _vp(ok), None, lr, _vp(ok), big - 1, None) == 5
+
+
+def test_static_scratch_update_rejects_sizes_beyond_its_limit(L):
+    import paper_2510_24061_amd as fq
+    ok = _vp(0x10000)
+    f = L.falqon_proxy_update_static
+    assert f(ok, ok, 256, 16400, 16, 4, ok, 1, None) == 7          # m beyond 16384
+    assert f(ok, ok, 256, 16384, 256, 300, ok, 1, None) == 7       # k * r beyond 65536
+    assert f(ok, ok, 256, 4096, 64, 0, ok, 1, None) == 2           # an ordinary shape error comes first
+    assert f(None, ok, 256, 4096, 64, 4, ok, 1, None) == 1
+    assert f(ok, _vp(0x10004), 256, 4096, 64, 4, ok, 1, None) == 3
+    assert fq.status_string(7).startswith("size beyond")
