@@ -7,12 +7,18 @@ A step is one pass of the whole hot path over one batch of synthetic input: meld
 melded backward (input gradient, adapter gradient, proxy-buffer step) and the row-wise proxy
 update, at the LLaMA-7B attention-projection shape (T = n = m = 4096, r = 64, k = 32).
 All inputs are resident in HBM before the timed region.  One JSON line is printed.
-The defaults (100 warm-up steps, 1000 timed steps, 0.2 s of GPU time) are long enough for the
-clocks to settle: the first few dozen steps after an idle period run about 10 % slower.
+
+How the step is timed: at least W warm-up steps and never less than 0.3 s of them (the clocks need a
+few dozen steps to settle after an idle period), then REPEATS blocks of exactly K steps, each block
+bracketed by a device synchronisation; `ms_per_step` is the median block.  The step is issued the
+way a training loop on this chip would issue a launch-bound inner loop: captured once into a HIP
+graph and replayed (`config.launch`); the same step issued call by call is reported beside it
+(`kernels.step_eager_ms`).
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -27,12 +33,16 @@ import workloads  # noqa: E402
 METRIC = "melded FP8 LoRA layer fwd+bwd tokens/sec and % FP8 MFMA peak, 7B shapes"
 FP8_PEAK_TFLOPS = 5000.0       # MI355X dense FP8 MFMA, published
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-# HBM bytes per launch of the forward GEMM kernel, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
-# runs of this command (profiles/bench_config2_pmc_hbm_traffic_and_mfma.md).
-GEMM_FWD_TRAFFIC_BYTES = 134.7e6   # 101.1 MB fetched (FETCH_SIZE x 1.998) + 33.6 MB written
+REPEATS = 5                    # timed blocks of K steps; the median is reported
+WARMUP_FLOOR_S = 0.3
+# Bytes that cross the L2 <-> fabric boundary per launch of the two product kernels at config 2:
+# rocprofv3 --pmc FETCH_SIZE (scaled by the plain-copy calibration) + WRITE_SIZE runs of this command;
+# the figures and the commands are in the committed summary named below.
+TRAFFIC_SOURCE = "profiles/bench_config2_pmc_hbm_traffic_and_mfma.md"
+TRAFFIC_BYTES = {"gemm_fwd_tail_kernel": None, "gemm_dx_tail_kernel": None}
 
 
-def _time_region(fn, iters):
+def _events(fn, iters):
     """Average milliseconds per call of fn over `iters` back-to-back calls, by HIP events on
     the stream the kernels are launched on (torch's current stream)."""
     start = torch.cuda.Event(enable_timing=True)
@@ -44,6 +54,50 @@ def _time_region(fn, iters):
     stop.record()
     stop.synchronize()
     return start.elapsed_time(stop) / iters
+
+
+def _median_events(fn, iters, repeats=REPEATS):
+    return statistics.median(_events(fn, iters) for _ in range(repeats))
+
+
+def _wall_blocks(fn, steps, repeats=REPEATS):
+    """`repeats` blocks of exactly `steps` calls, each bracketed by a device synchronisation; ms per call of every block."""
+    out = []
+    for _ in range(repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        out.append((time.perf_counter() - t0) * 1e3 / steps)
+    return out
+
+
+def _warm(fn, steps, floor_s=WARMUP_FLOOR_S):
+    """At least `steps` calls and at least `floor_s` seconds of them."""
+    done = 0
+    t0 = time.perf_counter()
+    while done < steps or time.perf_counter() - t0 < floor_s:
+        for _ in range(10):
+            fn()
+        done += 10
+        torch.cuda.synchronize()
+    return done
+
+
+def _capture(step):
+    """The step as a HIP graph.  The library's calls only enqueue kernels on the caller's stream (no
+    allocation, no memset, no synchronisation), so the whole step is capturable."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                 # code objects loaded, kernel attributes set, before the capture
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    return graph
 
 
 def cpu_baseline(cfg, d, sample_tokens, reps):
@@ -64,8 +118,8 @@ def cpu_baseline(cfg, d, sample_tokens, reps):
         oracle.proxy_update(b["delta_buf"], wcat, m, r, k)
     dt = time.perf_counter() - t0
     return {"value": reps * sample_tokens / dt, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"first {sample_tokens} of {cfg.T} tokens of the same workload as one batch, "
-                      f"fwd+bwd+update {reps} times ({dt:.1f} s)"}
+            "sample": f"first {sample_tokens} of {cfg.T} tokens of the same workload ({m}x{n}) as one batch, "
+                      f"fwd+bwd+update {reps} time(s) ({dt:.1f} s)"}
 
 
 def bf16_lora_layer(T, n, m, r, iters):
@@ -89,7 +143,7 @@ def bf16_lora_layer(T, n, m, r, iters):
 
     for _ in range(20):
         step()
-    return _time_region(step, iters)
+    return _events(step, iters)
 
 
 def library_fp8_gemm(T, n, m, iters):
@@ -106,7 +160,7 @@ def library_fp8_gemm(T, n, m, iters):
 
     for _ in range(20):
         run()
-    return _time_region(run, iters)
+    return _events(run, iters)
 
 
 def separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, iters):
@@ -151,7 +205,11 @@ def separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, iters):
 
     for _ in range(20):
         step()
-    return _time_region(step, iters)
+    return _events(step, iters)
+
+
+def _layer_flops(T, n, m, r):
+    return 2.0 * T * n * (m + r) + 2.0 * T * m * n + 2.0 * T * m * r
 
 
 def run_stack(fq, cfg, args):
@@ -185,37 +243,35 @@ def run_stack(fq, cfg, args):
             for layer in layers:
                 layer.update()
 
+    def cycle():                                   # one whole accumulation cycle
+        for i in range(acc):
+            train_step(i)
+
     # whole accumulation cycles; at most about 10 s of timed work and 2 s of warm-up
-    for i in range(acc):
-        train_step(i)
+    cycle()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(acc):
-        train_step(i)
+    cycle()
     torch.cuda.synchronize()
     est = (time.perf_counter() - t0) / acc
-    warm = max(min(args.warmup, int(2.0 / est)), acc) // acc * acc
-    steps = max(min(args.steps, int(10.0 / est)), acc) // acc * acc
-    for i in range(warm):
-        train_step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(steps):
-        train_step(i)
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
-    flops = sum(s.count * (2.0 * T * s.n * (s.m + r) + 2.0 * T * s.m * s.n + 2.0 * T * s.m * r) for s in cfg.layers)
+    warm = max(min(args.warmup, int(2.0 / est)), acc) // acc
+    cycles = max(min(args.steps, int(10.0 / est) // REPEATS), acc) // acc
+    _warm(cycle, warm)
+    blocks = [b / acc for b in _wall_blocks(cycle, cycles)]
+    ms_per_step = statistics.median(blocks)
+    flops = sum(s.count * _layer_flops(T, s.n, s.m, r) for s in cfg.layers)
     n_layers = len(layers)
     desc = ", ".join(f"{s.count}x {s.m}x{s.n}" for s in cfg.layers)
     out = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
-        "steps": steps, "warmup": warm, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": cycles * acc, "warmup": warm * acc, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "fp8 (E4M3 weights/activations, E5M2 gradients), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.cfg} ({cfg.name}): T={T}, {n_layers} layers ({desc}), r={r}, k={k}; "
                                f"fwd + bwd over all layers per step, proxy update of every layer each "
-                               f"{acc} step(s) (its time is spread over them)"},
-        "roofline": {"bound": "mfma", "kernel": "all FP8 GEMMs of the step (whole-step time, not a kernel time)",
+                               f"{acc} step(s) (its time is spread over them)",
+                   "launch": "call by call", "repeats": REPEATS, "ms_per_step_blocks": blocks},
+        "roofline": {"bound": "mfma", "kernel": "all FP8 products of the step (whole-step time, not a kernel time)",
                      "achieved": flops / (ms_per_step * 1e-3) / 1e12, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": flops / (ms_per_step * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, "traffic": None},
         "kernels": {"gemm_flops_per_step": flops, "layers": n_layers},
@@ -239,7 +295,7 @@ def rank_sweep(fq, cfg, args):
         layer.init_weights(w, a)
         for _ in range(3):
             layer.forward(x); layer.backward(dy, lr=cfg.lr)
-        ms_melded = _time_region(lambda: (layer.forward(x), layer.backward(dy, lr=cfg.lr)), it)
+        ms_melded = _events(lambda: (layer.forward(x), layer.backward(dy, lr=cfg.lr)), it)
         ms_sep = separate_path_fp8_lora_layer(fq, T, n, m, r, x, dy, w, a, it)
         ms_bf16 = bf16_lora_layer(T, n, m, r, it)
         rows.append({"r": r, "melded_fwd_bwd_ms": ms_melded, "separate_path_fp8_ms": ms_sep, "bf16_lora_ms": ms_bf16,
@@ -287,13 +343,78 @@ def decoder_block(fq, args):
 
         for _ in range(5):
             step()
-        out[name + "_ms"] = _time_region(step, max(10, min(args.steps, 50)))
+        out[name + "_ms"] = _events(step, max(10, min(args.steps, 50)))
         del block
     out["speedup"] = out["bf16_lora_ms"] / out["melded_fp8_ms"]
     out["backbone_gemm_flops"] = 2 * 2.0 * batch * seq * (4 * d_model * d_model + 3 * d_model * d_mlp)   # fwd + dX
     out["workload"] = (f"decoder block d={d_model}, heads={heads}, mlp={d_mlp}, tokens={batch}x{seq}, r={r}: "
                        "fwd+bwd, PyTorch RMSNorm / causal attention / SwiGLU between the projections")
     print(json.dumps({"decoder_block": out, "data": "synthetic"}))
+
+
+def _product_launches(fq, layer, x, dy, cfg):
+    """The two product launches of a step, each issued alone through falqon_fp8_gemm exactly as
+    falqon_melded_fwd / falqon_melded_bwd issue it (backbone product with the adapter's share as a
+    side job of its tiles), on the step's own operands.  Returns (forward fn, backward fn)."""
+    T, n, m, r = layer.T, layer.n, layer.m, layer.r
+    layer.forward(x)
+    layer.backward(dy, lr=cfg.lr)
+    oa_codes = torch.empty(T, r, dtype=torch.uint8, device="cuda")
+    s_oa = (448.0 / torch.clamp(layer.amax_oa, min=1e-12)).float()
+    s_tmp = torch.zeros(1, device="cuda")
+    fq.quantize(layer.o_a, fq.E4M3, oa_codes, s_tmp, layer.ws, scale_in=s_oa)
+    side_ws = torch.empty_like(layer.ws)
+    y_tmp, dx_tmp = torch.empty_like(layer.y), torch.empty_like(layer.dx)
+    wq_b, wq_a = layer.wq[:m], layer.wq[m:]
+
+    def fwd():
+        fq.fp8_gemm(layer.xq, fq.E4M3, wq_b, False, layer.s_x, layer.s_w, y_tmp, side=wq_a, side_ws=side_ws)
+
+    def bwd():
+        fq.fp8_gemm(layer.dyq, fq.E5M2, wq_b, True, layer.s_dy, layer.s_w, dx_tmp, side=oa_codes, side_ws=side_ws)
+
+    fwd(); bwd()                       # raises where the melded calls do not use these launches (small or odd shapes)
+    torch.cuda.synchronize()
+    assert torch.equal(y_tmp, layer.y) and torch.equal(dx_tmp, layer.dx)     # the same launches, the same bytes
+    return fwd, bwd
+
+
+def layer_summary(fq, cfg_id, layer_index, steps, cpu_tokens, with_cpu):
+    """One layer of another configuration, time-capped: ms per fwd + bwd + update (median of blocks),
+    its two product launches alone, and a CPU-oracle sample."""
+    cfg = workloads.CONFIGS[cfg_id]
+    d = workloads.config_layer_inputs(cfg_id, layer_index)
+    m, n, r, k, T = d["shape"].m, d["shape"].n, cfg.r, cfg.k, cfg.T
+    layer = fq.MeldedLinear(T, n, m, r, k, out_dtype=torch.bfloat16)
+    layer.init_weights(d["w"].cuda(), d["a"].cuda())
+    x, dy = d["x"].cuda(), d["dy"].cuda()
+
+    def step():
+        layer.forward(x)
+        layer.backward(dy, lr=cfg.lr)
+        layer.update()
+
+    graph = _capture(step)
+    _warm(graph.replay, 50)
+    blocks = _wall_blocks(graph.replay, steps)
+    ms = statistics.median(blocks)
+    fwd, bwd = _product_launches(fq, layer, x, dy, cfg)
+    ms_f, ms_b = _median_events(fwd, max(20, steps // 4)), _median_events(bwd, max(20, steps // 4))
+    fl_f, fl_b = 2.0 * T * n * (m + r), 2.0 * T * m * n + 2.0 * T * m * r
+    out = {"workload": f"config {cfg_id} layer {layer_index} ({d['shape'].name}): T={T}, n={n}, m={m}, r={r}, k={k}; "
+                       "fwd + bwd + proxy update per step, HIP graph replay",
+           "ms_per_step": ms, "ms_per_step_blocks": blocks, "tokens_per_s": T / (ms * 1e-3),
+           "products_flops": fl_f + fl_b,
+           "whole_step": {"TFLOP/s": (fl_f + fl_b) / (ms * 1e-3) / 1e12, "frac_fp8_peak": (fl_f + fl_b) / (ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS},
+           "product_launches": {
+               "forward_ms": ms_f, "backward_ms": ms_b,
+               "TFLOP/s": (fl_f + fl_b) / ((ms_f + ms_b) * 1e-3) / 1e12,
+               "frac_fp8_peak": (fl_f + fl_b) / ((ms_f + ms_b) * 1e-3) / 1e12 / FP8_PEAK_TFLOPS}}
+    del layer, x, dy, graph
+    torch.cuda.empty_cache()
+    if with_cpu:
+        out["cpu_baseline"] = cpu_baseline(cfg, d, min(cpu_tokens, T), 1)
+    return out
 
 
 def main():
@@ -304,8 +425,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload (2 = the headline LLaMA-7B attention projection; 3-5 run all their layers as a stack)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-context", action="store_true",
-                    help="skip the bf16 LoRA and separate-path FP8 LoRA comparison layers (profiling runs: their "
-                         "launches of the same GEMM kernel at other sizes would blur its per-kernel statistics)")
+                    help="skip the bf16 LoRA and separate-path FP8 LoRA comparison layers and the other configurations' "
+                         "layers (profiling runs: their launches of the same kernels at other sizes would blur the "
+                         "per-kernel statistics)")
     ap.add_argument("--decoder-block", action="store_true",
                     help="print the decoder-block context measurement instead of the benchmark line")
     ap.add_argument("--rank-sweep", action="store_true",
@@ -344,116 +466,112 @@ def main():
         layer.backward(dy, lr=cfg.lr)
         layer.update()
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    # ---- the timed region: the step as a replayed HIP graph, median of REPEATS blocks of K steps ----
+    graph = _capture(step)
+    warm_done = _warm(graph.replay, args.warmup)
+    blocks = _wall_blocks(graph.replay, args.steps)
+    ms_per_step = statistics.median(blocks)
+    # the same step issued call by call
+    _warm(step, 20, 0.05)
+    ms_eager = statistics.median(_wall_blocks(step, args.steps))
 
     # ---- per-call and per-kernel timing (HIP events on the launch stream) -------------------
-    it = max(10, args.steps)
-    ms_fwd = _time_region(lambda: layer.forward(x), it)
-    ms_bwd = _time_region(lambda: layer.backward(dy, lr=cfg.lr), it)
-    ms_upd = _time_region(lambda: layer.update(), it)
-    # the forward backbone product launched on its own (inside falqon_melded_fwd the same tile code shares
-    # its launch with the adapter's split-K tiles)
+    it = max(20, args.steps)
+    ms_fwd = _median_events(lambda: layer.forward(x), it)
+    ms_bwd = _median_events(lambda: layer.backward(dy, lr=cfg.lr), it)
+    ms_upd = _median_events(lambda: layer.update(), it)
+    # the two product launches of the step, each alone, exactly as the melded calls issue them
+    fwd_launch, bwd_launch = _product_launches(fq, layer, x, dy, cfg)
+    ms_prod_fwd = _median_events(fwd_launch, it)
+    ms_prod_bwd = _median_events(bwd_launch, it)
+    # the plain backbone products (no side job), for comparison
     y_tmp = torch.empty(T, m, dtype=torch.bfloat16, device="cuda")
-    ms_gemm_fwd = _time_region(lambda: fq.fp8_gemm(layer.xq, fq.E4M3, layer.wq[:m], False, layer.s_x, layer.s_w, y_tmp), it)
-    ms_gemm_dx = _time_region(lambda: fq.fp8_gemm(layer.dyq, fq.E5M2, layer.wq[:m], True, layer.s_dy, layer.s_w,
-                                                  layer.dx), it)
-    ms_gemm_const = ms_probe = tflops_probe = None
+    ms_gemm_fwd = _median_events(lambda: fq.fp8_gemm(layer.xq, fq.E4M3, layer.wq[:m], False, layer.s_x, layer.s_w, y_tmp), it)
+    ms_gemm_dx = _median_events(lambda: fq.fp8_gemm(layer.dyq, fq.E5M2, layer.wq[:m], True, layer.s_dy, layer.s_w, layer.dx), it)
+    ms_gemm_const = None
     if not args.no_context:
-        # the same launch on constant operands (every code = 1.0): identical instruction stream and memory traffic,
+        # the plain product on constant operands (every code = 1.0): identical instruction stream and memory traffic,
         # but almost no switching in the multipliers, so the chip holds its full clock - the rate the kernel's
         # schedule reaches when the power management does not intervene
         ones_x, ones_w = torch.full_like(layer.xq, 0x38), torch.full_like(layer.wq[:m], 0x38)
-        ms_gemm_const = _time_region(lambda: fq.fp8_gemm(ones_x, fq.E4M3, ones_w, False, layer.s_x, layer.s_w, y_tmp), it)
+        ms_gemm_const = _median_events(lambda: fq.fp8_gemm(ones_x, fq.E4M3, ones_w, False, layer.s_x, layer.s_w, y_tmp), it)
         del ones_x, ones_w
-        # the same matrix-core work as one backbone product (256 workgroups x 4 waves x 64 rounds x 16 instructions
-        # of 32x32x64) from registers only, on the workload's own codes: the rate the chip sustains with no memory
-        # traffic at all for these operand bits (its clock under matrix-core load falls as the bits toggle more)
-        sink = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
-        probe_rounds = n // 64
-        ms_probe = _time_region(lambda: fq.mfma_probe(layer.xq, layer.wq, 256, probe_rounds, sink), it)
-        tflops_probe = 256 * 4 * probe_rounds * 16 * 2.0 * 32 * 32 * 64 / (ms_probe * 1e-3) / 1e12
-        del sink
     # optimizer variant of the buffer step: bwd without the SGD step, global-norm term, AdamW into the buffer
     sum_sq = torch.zeros(1, dtype=torch.float64, device="cuda")
     layer.adamw_step(1, sum_sq)                       # allocates the moments
-    ms_sqnorm = _time_region(lambda: fq.grad_sqnorm(layer.d_b, sum_sq, layer.ws), it)
-    ms_adamw = _time_region(lambda: layer.adamw_step(2, sum_sq), it)
-    # variant of the adapter gradient with O_A kept in bf16 (its two launches, outside the paired launch)
+    ms_sqnorm = _events(lambda: fq.grad_sqnorm(layer.d_b, sum_sq, layer.ws), it)
+    ms_adamw = _events(lambda: layer.adamw_step(2, sum_sq), it)
+    # variant of the adapter gradient with O_A kept in bf16 (its two launches)
     db_tmp = torch.empty(m, r, device="cuda")
-    ms_db_wide = _time_region(lambda: fq.db_bf16(layer.dyq, layer.s_dy, layer.o_a, db_tmp, None, 0.0, layer.ws), it)
+    ms_db_wide = _events(lambda: fq.db_bf16(layer.dyq, layer.s_dy, layer.o_a, db_tmp, None, 0.0, layer.ws), it)
     del db_tmp
     layer.delta_buf.zero_()
     s_tmp = torch.zeros(1, device="cuda")
-    ms_quant = _time_region(lambda: fq.quantize(x, fq.E4M3, layer.xq, s_tmp, layer.ws), it)
+    ms_quant = _median_events(lambda: fq.quantize(x, fq.E4M3, layer.xq, s_tmp, layer.ws), it)
     del y_tmp
 
-    flops_fwd = 2.0 * T * n * m
     # one plain device-to-device copy of known size: the reference that scales the FETCH_SIZE /
     # WRITE_SIZE counters when this command runs under rocprofv3 --pmc
     calib = torch.empty_like(x)
     calib.copy_(x)
     torch.cuda.synchronize()
     del calib
-    flops_dx = 2.0 * T * m * n
-    flops_db = 2.0 * T * m * r
-    tflops_fwd = flops_fwd / (ms_gemm_fwd * 1e-3) / 1e12
-    tflops_dx = flops_dx / (ms_gemm_dx * 1e-3) / 1e12
+
+    flops_fwd = 2.0 * T * n * (m + r)              # backbone product + adapter columns: one launch
+    flops_bwd = 2.0 * T * m * n + 2.0 * T * m * r  # input gradient + adapter gradient: one launch
+    flops_plain = 2.0 * T * n * m
     quant_bytes = 3.0 * T * n                      # read bf16 once (second read is cache-served), write FP8
     upd_bytes = 4.0 * m * r + 2.0 * k * n + r * n + 8.0 * k * r   # scores + selected rows in/out + adapter rows + buffer rows
-    # The backbone product launched on its own.  Inside falqon_melded_fwd the same tile code runs in
-    # gemm_fwd_pair_kernel, one launch that also carries the adapter's split-K tiles (see kernels).
-    roofline = {"bound": "mfma", "kernel": "gemm_fp8_kernel<2,2,4,4,false,0> (forward, X~ . W~^T, 256 tiles of 256x256)",
-                "achieved": tflops_fwd, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-                "frac": tflops_fwd / FP8_PEAK_TFLOPS, "traffic": GEMM_FWD_TRAFFIC_BYTES,
-                "flops_per_launch": flops_fwd, "avg_launch_ms": ms_gemm_fwd}
-    if not args.no_context:
-        roofline["same_launch_constant_operands"] = {
-            "ms": ms_gemm_const, "TFLOP/s": flops_fwd / (ms_gemm_const * 1e-3) / 1e12,
-            "frac": flops_fwd / (ms_gemm_const * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
-            "note": "same kernel, grid and traffic with all codes = 1.0: the clock stays at its nominal value; the gap "
-                    "to 'achieved' is the clock the chip grants for the workload's operand bits"}
-        roofline["register_only_mfma_loop"] = {
-            "TFLOP/s": tflops_probe, "ms": ms_probe, "frac_of_peak": tflops_probe / FP8_PEAK_TFLOPS,
-            "achieved_over_loop": tflops_fwd / tflops_probe,
-            "note": "same instruction count as the product, operands = this workload's FP8 codes held in registers, "
-                    "no LDS/cache/HBM traffic: what the chip's power management lets the matrix cores sustain"}
+    # The dominant kernel of the step: the forward product launch (the backward one takes about as long).
+    dominant_fwd = ms_prod_fwd >= ms_prod_bwd
+    dom_ms, dom_flops = (ms_prod_fwd, flops_fwd) if dominant_fwd else (ms_prod_bwd, flops_bwd)
+    traffic = TRAFFIC_BYTES["gemm_fwd_tail_kernel" if dominant_fwd else "gemm_dx_tail_kernel"]
+    roofline = {
+        "bound": "mfma",
+        "kernel": ("gemm_fwd_tail_kernel (the product launch of falqon_melded_fwd: 256 tiles of 256x256 of X~ W~^T, each "
+                   "followed by its share of O_A)") if dominant_fwd else
+                  ("gemm_dx_tail_kernel (the product launch of falqon_melded_bwd: 256 tiles of 256x256 of dY~ W~, each "
+                   "followed by its share of dB)"),
+        "achieved": dom_flops / (dom_ms * 1e-3) / 1e12, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": dom_flops / (dom_ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
+        "traffic": traffic, "traffic_source": TRAFFIC_SOURCE + " (rocprofv3 --pmc FETCH_SIZE x calibration + WRITE_SIZE of "
+                                              "this command: bytes per launch at the L2-fabric boundary, a recorded figure)",
+        "flops_per_launch": dom_flops, "avg_launch_ms": dom_ms,
+        "how": "the launch issued alone through falqon_fp8_gemm(side=...) with the step's own operands, back to back, "
+               "HIP events on the launch stream, median of %d runs" % REPEATS,
+    }
+    if ms_gemm_const is not None:
+        roofline["plain_product_constant_operands"] = {
+            "ms": ms_gemm_const, "TFLOP/s": flops_plain / (ms_gemm_const * 1e-3) / 1e12,
+            "frac": flops_plain / (ms_gemm_const * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
+            "note": "the plain backbone product with all codes = 1.0 (same kernel, grid and traffic): the clock stays at its "
+                    "nominal value; the gap to kernels.gemm_fwd_plain is the clock the chip grants for the workload's bits"}
+    tf = lambda fl, ms: fl / (ms * 1e-3) / 1e12
     kernels = {
-        "gemm_fwd": {"ms": ms_gemm_fwd, "TFLOP/s": tflops_fwd, "frac_fp8_peak": tflops_fwd / FP8_PEAK_TFLOPS},
-        "gemm_dx": {"ms": ms_gemm_dx, "TFLOP/s": tflops_dx, "frac_fp8_peak": tflops_dx / FP8_PEAK_TFLOPS},
+        "step_graph_ms": ms_per_step, "step_eager_ms": ms_eager,
+        "product_launch_fwd": {"ms": ms_prod_fwd, "flops": flops_fwd, "TFLOP/s": tf(flops_fwd, ms_prod_fwd),
+                               "frac_fp8_peak": tf(flops_fwd, ms_prod_fwd) / FP8_PEAK_TFLOPS},
+        "product_launch_bwd": {"ms": ms_prod_bwd, "flops": flops_bwd, "TFLOP/s": tf(flops_bwd, ms_prod_bwd),
+                               "frac_fp8_peak": tf(flops_bwd, ms_prod_bwd) / FP8_PEAK_TFLOPS},
+        "product_launches": {"ms": ms_prod_fwd + ms_prod_bwd, "flops": flops_fwd + flops_bwd,
+                             "TFLOP/s": tf(flops_fwd + flops_bwd, ms_prod_fwd + ms_prod_bwd),
+                             "frac_fp8_peak": tf(flops_fwd + flops_bwd, ms_prod_fwd + ms_prod_bwd) / FP8_PEAK_TFLOPS,
+                             "note": "all three products of a step (forward with adapter columns, dX, dB) over their two launches"},
+        "gemm_fwd_plain": {"ms": ms_gemm_fwd, "TFLOP/s": tf(flops_plain, ms_gemm_fwd), "frac_fp8_peak": tf(flops_plain, ms_gemm_fwd) / FP8_PEAK_TFLOPS,
+                           "note": "backbone product alone, no side job (isolated launch, not part of the step)"},
+        "gemm_dx_plain": {"ms": ms_gemm_dx, "TFLOP/s": tf(flops_plain, ms_gemm_dx), "frac_fp8_peak": tf(flops_plain, ms_gemm_dx) / FP8_PEAK_TFLOPS},
         "quantize_x": {"ms": ms_quant, "GB/s": quant_bytes / (ms_quant * 1e-3) / 1e9,
                        "frac_hbm_peak": quant_bytes / (ms_quant * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "proxy_update": {"ms": ms_upd, "GB/s": upd_bytes / (ms_upd * 1e-3) / 1e9,
                          "frac_hbm_peak": upd_bytes / (ms_upd * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "note": "three dependent launches over 1.6 MB: latency bound"},
+                         "note": "dependent launches over 1.6 MB: latency bound"},
         "adamw_buffer_step": {"grad_sqnorm_ms": ms_sqnorm, "adamw_delta_ms": ms_adamw,
                               "bytes": 28.0 * m * r, "GB/s": 28.0 * m * r / (ms_adamw * 1e-3) / 1e9,
                               "note": "optional replacement of the SGD buffer step inside melded_bwd; not in the timed step"},
-        "db_bf16_variant": {"ms": ms_db_wide, "flops": flops_db,
+        "db_bf16_variant": {"ms": ms_db_wide, "flops": 2.0 * T * m * r,
                             "note": "dB = dy~^T O_A with O_A kept in bf16 (bf16 matrix cores), partial pass + ordered sum as "
                                     "two launches of their own; not in the timed step"},
-        "fwd_after_quantize": {"ms_derived": ms_fwd - ms_quant, "flops": 2.0 * T * n * (m + r),
-                               "TFLOP/s": 2.0 * T * n * (m + r) / ((ms_fwd - ms_quant) * 1e-3) / 1e12,
-                               "note": "melded_fwd minus the quantizer: gemm_fwd_pair_kernel (backbone tiles + adapter "
-                                       "split-K tiles in one launch) + the ordered sum of the adapter partials"},
-        "bwd_after_quantize": {"ms_derived": ms_bwd - ms_quant, "flops": flops_dx + flops_db,
-                               "TFLOP/s": (flops_dx + flops_db) / ((ms_bwd - ms_quant) * 1e-3) / 1e12,
-                               "note": "melded_bwd minus the quantizer (E5M2 pass costs what the E4M3 pass does): "
-                                       "gemm_dx_db_pair_kernel + the ordered sum of the dB partials with the buffer step"},
-        "all_products": {"flops": 2.0 * T * n * (m + r) + flops_dx + flops_db,
-                         "ms_derived": ms_fwd + ms_bwd - 2.0 * ms_quant,
-                         "TFLOP/s": (2.0 * T * n * (m + r) + flops_dx + flops_db) / ((ms_fwd + ms_bwd - 2.0 * ms_quant) * 1e-3) / 1e12,
-                         "frac_fp8_peak": (2.0 * T * n * (m + r) + flops_dx + flops_db) / ((ms_fwd + ms_bwd - 2.0 * ms_quant) * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
-                         "note": "the three products of a step (forward with adapter columns, dX, dB) over everything "
-                                 "in the two calls except the quantizer passes"},
         "calls": {"melded_fwd_ms": ms_fwd, "melded_bwd_ms": ms_bwd, "proxy_update_ms": ms_upd},
-        "gemm_flops": {"fwd_backbone": flops_fwd, "fwd_adapter": 2.0 * T * n * r, "dx": flops_dx, "db": flops_db},
     }
 
     ms_fwd_bwd = ms_fwd + ms_bwd
@@ -474,15 +592,23 @@ def main():
 
     out = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": warm_done, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "fp8 (E4M3 weights/activations, E5M2 gradients), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.cfg} ({cfg.name}): T={T}, n={n}, m={m}, r={r}, k={k}; "
-                               "fwd + bwd + proxy update per step"},
+                               "fwd + bwd + proxy update per step",
+                   "launch": "HIP graph replay of the step (captured once)", "repeats": REPEATS,
+                   "ms_per_step_blocks": blocks},
         "roofline": roofline, "kernels": kernels, "context": context,
     }
+    del layer, graph
+    torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, d, min(args.cpu_sample_tokens, T), args.cpu_reps)
+    if not args.no_context and args.config == 2:
+        # the two MLP projections of the same model (config 3), time-capped
+        sub_steps = max(20, min(200, args.steps))
+        out["configs"] = [layer_summary(fq, 3, li, sub_steps, 1024, not args.no_cpu_baseline) for li in (0, 1)]
     print(json.dumps(out))
 
 

@@ -59,7 +59,8 @@ def lib():
         L.falqon_db_bf16.restype = c.c_int
         L.falqon_db_bf16.argtypes = [vp, f32p, vp, i64, i64, i64, vp, vp, c.c_float, vp, c.c_size_t, vp]
         L.falqon_fp8_gemm.restype = c.c_int
-        L.falqon_fp8_gemm.argtypes = [vp, c.c_int, vp, c.c_int, i64, i64, i64, f32p, f32p, vp, c.c_int, vp]
+        L.falqon_fp8_gemm.argtypes = [vp, c.c_int, vp, c.c_int, i64, i64, i64, f32p, f32p, vp, c.c_int,
+                                      vp, i64, vp, c.c_size_t, vp]
         L.falqon_grad_sqnorm.restype = c.c_int
         L.falqon_grad_sqnorm.argtypes = [f32p, i64, vp, vp, c.c_size_t, vp]
         L.falqon_adamw_delta.restype = c.c_int
@@ -167,13 +168,17 @@ def proxy_update_static(delta_buf, wq, m: int, r: int, k: int, idx_out, clear_se
     _check(st, "falqon_proxy_update_static")
 
 
-def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c) -> None:
-    """C = A . op(B) / (s_a s_b): a [M,K] FP8; b E4M3 [N,K] or, with b_is_kn, [K,N]."""
-    _dev(a, b, s_a, s_b, c)
+def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c, side=None, side_ws=None) -> None:
+    """C = A . op(B) / (s_a s_b): a [M,K] FP8; b E4M3 [N,K] or, with b_is_kn, [K,N].
+    With `side` (adapter rows [r,K], or O_A codes [M,r] when b_is_kn) and a workspace it is the product
+    launch of the melded forward / backward call, adapter partials included."""
+    _dev(a, b, s_a, s_b, c, side, side_ws)
     M, K = a.shape
     N = b.shape[1] if b_is_kn else b.shape[0]
+    r = 0 if side is None else (side.shape[1] if b_is_kn else side.shape[0])
     st = lib().falqon_fp8_gemm(_p(a), a_fmt, _p(b), 1 if b_is_kn else 0, M, N, K, _p(s_a), _p(s_b), _p(c),
-                               _dtype_code(c), _stream())
+                               _dtype_code(c), _p(side), r, _p(side_ws),
+                               0 if side_ws is None else side_ws.numel() * side_ws.element_size(), _stream())
     _check(st, "falqon_fp8_gemm")
 
 

@@ -39,9 +39,8 @@ __device__ __forceinline__ float buffer_step(float buf, float lr, float g)
 }
 
 // dB = (sum of partials, split ascending) / (s_dy * s_oa);  delta_buf += -lr * dB
-template <int SPLITS>
 __global__ void __launch_bounds__(kThreads)
-db_reduce_kernel(const float* __restrict__ partial, int64_t count,
+db_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count,
                  const float* __restrict__ s_dy, const float* __restrict__ amax_oa,
                  float* __restrict__ d_b, float* delta_buf, float lr)
 {
@@ -49,21 +48,19 @@ db_reduce_kernel(const float* __restrict__ partial, int64_t count,
     const float inv = 1.0f / ((*s_dy) * s_oa_scale);
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * 4;
     for (int64_t e = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4; e < count; e += stride) {
-        float4 s;
-        {
-            constexpr int B = SPLITS < 8 ? SPLITS : 8;                // loads in flight per batch
+        constexpr int B = 8;                                          // loads in flight per batch
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int sp0 = 0; sp0 < splits; sp0 += B) {
             float4 v[B];
 #pragma unroll
-            for (int u = 0; u < B; ++u) v[u] = *reinterpret_cast<const float4*>(partial + u * count + e);
-            s = v[0];
+            for (int u = 0; u < B; ++u) {
+                const int sp = sp0 + u < splits ? sp0 + u : splits - 1;  // beyond the range: a valid address, value unused
+                v[u] = *reinterpret_cast<const float4*>(partial + sp * count + e);
+            }
 #pragma unroll
-            for (int u = 1; u < B; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
-#pragma unroll
-            for (int sp0 = B; sp0 < SPLITS; sp0 += B) {
-#pragma unroll
-                for (int u = 0; u < B; ++u) v[u] = *reinterpret_cast<const float4*>(partial + (sp0 + u) * count + e);
-#pragma unroll
-                for (int u = 0; u < B; ++u) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+            for (int u = 0; u < B; ++u) {
+                if (sp0 + u == 0) s = v[u];
+                else if (sp0 + u < splits) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
             }
         }
         s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
@@ -127,16 +124,9 @@ hipError_t launch_db_reduce(const DbArgs& d, const float* s_dy, float* d_b, floa
     const int64_t count = m * r;
     int64_t blocks = (count / 4 + kThreads - 1) / kThreads;
     if (blocks < 1) blocks = 1;
-    const unsigned nb = static_cast<unsigned>(blocks);
-    switch (splits) {
-        case 1: db_reduce_kernel<1><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
-        case 2: db_reduce_kernel<2><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
-        case 4: db_reduce_kernel<4><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
-        case 8: db_reduce_kernel<8><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
-        case 16: db_reduce_kernel<16><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
-        case 32: db_reduce_kernel<32><<<nb, kThreads, 0, stream>>>(partials, count, s_dy, amax_oa, d_b, delta_buf, lr); break;
-        default: return hipErrorInvalidValue;                // db_splits() only returns powers of two
-    }
+    if (splits < 1) return hipErrorInvalidValue;
+    db_reduce_kernel<<<static_cast<unsigned>(blocks), kThreads, 0, stream>>>(partials, splits, count, s_dy, amax_oa, d_b,
+                                                                          delta_buf, lr);
     return hipGetLastError();
 }
 

@@ -10,16 +10,22 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 WsLayout ws_layout(int64_t T, int64_t n, int64_t m, int64_t r)
 {
-    (void)n;
     WsLayout w;
     size_t off = 0;
+    // partial counts: the larger of what the two ways of forming each adapter product need
+    const OaTailPlan po = plan_oa_tail(T, n, m, r);
+    const DbTailPlan pd = plan_db_tail(T, n, m, r);
+    int oa_parts = oa_splits(T, r), db_parts = db_splits(T, m);
+    if (po.use && po.splits > oa_parts) oa_parts = po.splits;
+    if (pd.use && pd.groups > db_parts) db_parts = pd.groups;
     w.amax_partials = off; off = align_up(off + sizeof(float) * kMaxAmaxBlocks, 256);
     w.scores = off;        off = align_up(off + sizeof(double) * static_cast<size_t>(m), 256);
     w.delta_sel = off;     off = align_up(off + sizeof(float) * static_cast<size_t>(m) * static_cast<size_t>(r), 256);
-    w.db_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(db_splits(T, m)) *
+    w.db_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(db_parts) *
                                                     static_cast<size_t>(m) * static_cast<size_t>(r), 256);
-    w.oa_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(oa_splits(T, r)) *
+    w.oa_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(oa_parts) *
                                                     static_cast<size_t>(T) * static_cast<size_t>(r), 256);
+    w.oa_codes = off;      off = align_up(off + static_cast<size_t>(T) * static_cast<size_t>(r), 256);
     w.total = off;
     return w;
 }
@@ -138,13 +144,26 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
         e = launch_gemm(g, st);
         return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
     }
-    // O_A <- x~ A~^T / (s_w s_x): same kernel, K split over workgroups, fp32 partials, then one
-    // pass that adds them in order, rounds to bf16 and takes the maximum.  Nothing orders the two
-    // products, so when the backbone product runs on the large tiles both go out as one launch.
+    // O_A <- x~ A~^T / (s_w s_x) as fp32 partials over K slices, then one pass that adds them in
+    // order, rounds to bf16 and takes the maximum.  On the large tiles every backbone workgroup
+    // forms a share of the partials as a side job after its own tile.
+    float* part = reinterpret_cast<float*>(w8 + L.oa_partials);
+    const OaTailPlan po = plan_oa_tail(T, n, m, r);
+    if (po.use) {
+        TailArgs t;
+        t.side = wq + m * n; t.r = r; t.partial = part; t.splits = po.splits; t.steps_per_split = po.steps_per_split;
+        t.row_parts = po.row_parts;
+        e = launch_gemm_fwd_tail(g, t, st);
+        if (e != hipSuccess) return FALQON_ERR_HIP;
+        e = launch_sum_partials_bf16(part, po.splits, T * r, static_cast<uint16_t*>(o_a),
+                                     reinterpret_cast<uint32_t*>(amax_oa), st);
+        return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+    }
+    // Otherwise: the same GEMM kernel on the adapter rows, K split over workgroups.  Nothing orders
+    // the two products, so when the backbone product runs on the large tiles both go out as one launch.
     const int splits = oa_splits(T, r);
     int64_t kps = (n + splits - 1) / splits;
     kps = (kps + 127) / 128 * 128;
-    float* part = reinterpret_cast<float*>(w8 + L.oa_partials);
     GemmArgs h;
     h.a = xq; h.lda = n; h.a_fmt = 0;
     h.b = wq + m * n; h.ldb = n; h.b_is_kn = 0;
@@ -187,9 +206,12 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
     hipStream_t st = static_cast<hipStream_t>(stream);
     uint8_t* w8 = static_cast<uint8_t*>(ws);
 
-    // dy~, s_dy <- Q_E5M2(dy)
+    // dy~, s_dy <- Q_E5M2(dy).  When the adapter gradient is formed by side jobs of the dX tiles, the
+    // cast pass also casts the saved O_A to E4M3 (its maximum is known from the forward pass).
+    const DbTailPlan pd = dx ? plan_db_tail(T, n, m, r) : DbTailPlan{false, 0};
+    SideCast sc{static_cast<const uint16_t*>(o_a), amax_oa, w8 + L.oa_codes, T * r};
     hipError_t e = launch_quantize(dy, FALQON_BF16, T, m, m, FALQON_E5M2, nullptr, dyq, m, s_dy, nullptr,
-                                   reinterpret_cast<float*>(w8 + L.amax_partials), nullptr, st);
+                                   reinterpret_cast<float*>(w8 + L.amax_partials), nullptr, st, pd.use ? &sc : nullptr);
     if (e != hipSuccess) return FALQON_ERR_HIP;
 
     // dX <- dy~ W~ / (s_dy s_w): the backbone rows of the concatenated weight, read as [K = m, N = n]
@@ -203,8 +225,12 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
     // dB <- dy~^T O_A~ / (s_dy s_oa);  DeltaBuffer += -lr dB.  Its partial pass reads only dy~ and
     // O_A, so nothing orders it against the dX product: on the large tiles both go out as one launch.
     const DbArgs d = make_db_args(dyq, o_a, amax_oa, T, m, r, reinterpret_cast<float*>(w8 + L.db_partials),
-                                  db_splits(T, m));
-    if (!dx) {
+                                  pd.use ? pd.groups : db_splits(T, m));
+    if (pd.use) {
+        TailArgs t;
+        t.side = w8 + L.oa_codes; t.r = r; t.partial = d.partial; t.splits = 0; t.steps_per_split = 0; t.row_parts = 1;
+        e = launch_gemm_dx_tail(g, t, st);
+    } else if (!dx) {
         e = launch_db_partial(d, st);                      // the layer's input needs no gradient
     } else if (gemm_dx_db_pair_supported(g)) {
         e = launch_gemm_dx_db_pair(g, d, st);
@@ -270,7 +296,8 @@ falqon_status falqon_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t 
 
 falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t* b, int b_is_kn,
                               int64_t M, int64_t N, int64_t K, const float* s_a, const float* s_b,
-                              void* c, falqon_dtype ct, void* stream)
+                              void* c, falqon_dtype ct,
+                              const uint8_t* side, int64_t r, void* side_ws, size_t side_ws_bytes, void* stream)
 {
     if (a_fmt != FALQON_E4M3 && a_fmt != FALQON_E5M2) return FALQON_ERR_ENUM;
     if (ct != FALQON_BF16 && ct != FALQON_F32) return FALQON_ERR_ENUM;
@@ -286,7 +313,37 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
     g.sa = s_a; g.sb = s_b;
     g.c0 = c; g.ldc0 = N; g.c0_is_f32 = (ct == FALQON_F32); g.n_split = N;
     g.c1 = nullptr; g.ldc1 = 0; g.amax1 = nullptr;
-    hipError_t e = launch_gemm(g, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!side) {
+        hipError_t e = launch_gemm(g, st);
+        return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+    }
+    // The product launch of a melded call: the same product with the adapter's share as a side job.
+    // The layer's (n, m) are (K, N) in the forward orientation and (N, K) in the input-gradient one.
+    const int64_t n = b_is_kn ? N : K, m = b_is_kn ? K : N;
+    if (bad_layer_shape(M, n, m, r)) return FALQON_ERR_SHAPE;
+    if ((b_is_kn != 0) != (a_fmt == FALQON_E5M2)) return FALQON_ERR_ENUM;
+    if (misaligned(side)) return FALQON_ERR_ALIGN;
+    const WsLayout L = ws_layout(M, n, m, r);
+    if (!side_ws || side_ws_bytes < L.total) return FALQON_ERR_WORKSPACE;
+    if (misaligned(side_ws)) return FALQON_ERR_ALIGN;
+    uint8_t* w8 = static_cast<uint8_t*>(side_ws);
+    TailArgs t;
+    t.side = side; t.r = r; t.splits = 0; t.steps_per_split = 0; t.row_parts = 1;
+    hipError_t e;
+    if (!b_is_kn) {
+        const OaTailPlan po = plan_oa_tail(M, n, m, r);
+        const int64_t tile = gemm_tile_n(M, m + r);
+        if (!po.use || (m + r + tile - 1) / tile == (m + tile - 1) / tile) return FALQON_ERR_SHAPE;
+        t.partial = reinterpret_cast<float*>(w8 + L.oa_partials); t.splits = po.splits; t.steps_per_split = po.steps_per_split;
+        t.row_parts = po.row_parts;
+        e = launch_gemm_fwd_tail(g, t, st);
+    } else {
+        const DbTailPlan pd = plan_db_tail(M, n, m, r);
+        if (!pd.use) return FALQON_ERR_SHAPE;
+        t.partial = reinterpret_cast<float*>(w8 + L.db_partials);
+        e = launch_gemm_dx_tail(g, t, st);
+    }
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 

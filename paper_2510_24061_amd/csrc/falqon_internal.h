@@ -20,6 +20,7 @@ struct WsLayout {
     size_t delta_sel;       // float[m][r]: buffer rows picked by the proxy update, in rank order
     size_t db_partials;     // float[splits][m][r]
     size_t oa_partials;     // float[splits][T][r]
+    size_t oa_codes;        // uint8[T][r]: the saved O_A cast to E4M3 for the adapter gradient
     size_t total;
 };
 WsLayout ws_layout(int64_t T, int64_t n, int64_t m, int64_t r);
@@ -28,10 +29,13 @@ int db_splits(int64_t T, int64_t m);
 // ---- quantizer (quantize.hip) ------------------------------------------------------------
 // Two launches: per-block partial maxima, then scale + cast.  `zero_word` (nullable) is a
 // device word the cast pass clears, used to reset the running maximum of O_A.
+// `side` (nullable): a small dense bf16 tensor of `count` elements (a multiple of 16) with a known
+// maximum that the cast pass casts to E4M3 along the way, q = cast(x * (448 / max(*amax, 1e-12f))).
+struct SideCast { const uint16_t* x; const float* amax; uint8_t* q; int64_t count; };
 hipError_t launch_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t cols, int64_t ld_x,
                            falqon_fmt fmt, const float* scale_in, uint8_t* q, int64_t ld_q,
                            float* scale_out, float* amax_out, float* partials, uint32_t* zero_word,
-                           hipStream_t stream);
+                           hipStream_t stream, const SideCast* side = nullptr);
 // Clears one device word with a kernel (a memset node is not safe inside a captured graph here).
 hipError_t launch_zero_word(uint32_t* w, hipStream_t stream);
 
@@ -56,6 +60,22 @@ int64_t gemm_tile_n(int64_t M, int64_t N);   // width of the output tiles launch
 // [N,K], E4M3.  Results are those of launch_gemm(g) and launch_gemm(h).
 bool gemm_fwd_pair_supported(const GemmArgs& g, const GemmArgs& h);
 hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_t stream);
+
+// Side job that every 256x256 backbone tile performs after its own tile (gemm.hip).
+//   forward launch:        side = adapter rows A~ [r][K] (row stride g.ldb); partial[splits][M][r], rescaled;
+//                          tile columns in sets of row_parts: set s < splits covers K-steps
+//                          [s * steps_per_split, +steps_per_split), each member a part of the token rows
+//   input-gradient launch: side = O_A codes [T][r] (E4M3, cast by the dy quantizer's cast pass);
+//                          partial[groups][m][r], raw sums; splits / steps_per_split unused
+struct TailArgs {
+    const uint8_t* side; int64_t r; float* partial; int splits; int steps_per_split; int row_parts;
+};
+struct OaTailPlan { bool use; int splits; int steps_per_split; int row_parts; };
+struct DbTailPlan { bool use; int groups; };
+OaTailPlan plan_oa_tail(int64_t T, int64_t n, int64_t m, int64_t r);     // forward of a [T,n] x [m+r,n] layer
+DbTailPlan plan_db_tail(int64_t T, int64_t n, int64_t m, int64_t r);     // backward of the same layer
+hipError_t launch_gemm_fwd_tail(const GemmArgs& g, const TailArgs& t, hipStream_t stream);
+hipError_t launch_gemm_dx_tail(const GemmArgs& g, const TailArgs& t, hipStream_t stream);
 
 // ---- O_A from split-K partials (partials.hip) ---------------------------------------------------
 // out[count] (bf16) = sum over splits of partial[split][count]; folds max|out| into *amax.

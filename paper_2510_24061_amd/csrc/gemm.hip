@@ -82,6 +82,249 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));
 }
 
+// ---- side jobs of a 256x256 backbone tile ---------------------------------------------------------
+// The adapter's two small products (O_A = x~ A~^T in the forward launch, dB = dy~^T O_A~ in the
+// input-gradient launch) are 1.5 % of a step's flops.  Run as tiles of their own before the backbone
+// tiles they cost a whole round of latency-bound workgroups, one per CU.  Instead every backbone
+// workgroup takes a small share of them BEFORE its own tile, while the accumulation registers are
+// still free: the share's operands are fetched straight into LDS together with the tile's first
+// stage (so the two memory latencies overlap), multiplied, and written out as an fp32 partial that
+// a later pass adds in a fixed order.  The partial's stores then drain, and leave the L2, under the
+// tile's main loop; issued at the end of the kernel they would sit in front of its completion.
+// LDS: the tile's first stage takes ring slot 0 of each operand; the share's operands take slots 1
+// and 2 of the left ring (64 KB) and slot 1 of the right ring (32 KB), which the tile's second
+// stage overwrites only after the share is done.
+__device__ __forceinline__ void dma16_to_lds(const uint8_t* src, uint8_t* dst_wave_uniform)
+{
+    __builtin_amdgcn_global_load_lds(FQ_GLOBAL_PTR(src), FQ_LDS_PTR(dst_wave_uniform), 16, 0, 0);
+}
+
+// 32x32x64 operand of lane `lane` from a K-contiguous tile (128-byte rows, swizzle swz_kc)
+__device__ __forceinline__ v8i read_kc_tile(const uint8_t* tile, int row, int kh, int lane)
+{
+    const int cb = kh * 4 + (lane >> 5) * 2;
+    const int sw = swz_kc(row);
+    const uint8_t* base = tile + row * BK;
+    const v4i lo = *reinterpret_cast<const v4i*>(base + ((cb ^ sw) << 4));
+    const v4i hi = *reinterpret_cast<const v4i*>(base + (((cb + 1) ^ sw) << 4));
+    v8i r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return r;
+}
+
+// Forward: the tile columns of a tile row are taken in sets of Q (Q = t.row_parts, 1 or 2).  Set s
+// < splits covers K-steps [s * steps_per_split, +steps_per_split); member h of the set multiplies
+// token rows [h * 256 / Q, +256 / Q) of the tile row with the adapter rows over those K-steps and
+// writes them to partial[s][token][rank] (rescaled).  Q = 2 halves the number of partials for the
+// same work per workgroup.  LDS chunk: 2 Q K-steps of the 256 / Q token rows (64 KB in lds_x) and
+// of up to 64 adapter rows (16 Q KB in lds_a).
+static_assert(2 * 64 * BK * 2 <= 32 * 1024, "the adapter rows of a chunk fit one slot of the right ring");
+
+__device__ __forceinline__ bool oa_side_active(const TailArgs& t, int tile_n) { return tile_n / t.row_parts < t.splits; }
+
+template <int Q>
+__device__ __forceinline__ void oa_side_fetch(const TailArgs& t, const GemmArgs& g, int64_t m0, int tile_n, int c,
+                                              uint8_t* lds_x, uint8_t* lds_a, int wave, int lane)
+{
+    constexpr int ROWS = 256 / Q, STEPS = 2 * Q;                  // per chunk
+    const int KT = static_cast<int>((g.K + BK - 1) / BK);
+    const int set = tile_n / Q;
+    int s_end = (set + 1) * t.steps_per_split;
+    if (s_end > KT) s_end = KT;
+    const int s0 = set * t.steps_per_split + c * STEPS;
+    const int64_t row0 = m0 + (tile_n % Q) * ROWS;
+    const int r = static_cast<int>(t.r);
+#pragma unroll
+    for (int j = 0; j < STEPS; ++j) {
+        if (s0 + j >= s_end) break;
+        const int64_t k0 = static_cast<int64_t>(s0 + j) * BK;
+#pragma unroll
+        for (int it = 0; it < ROWS / 8 / 4; ++it) {               // token rows, 8 per wave instruction
+            const int i = it * 4 + wave;
+            const int row = i * 8 + (lane >> 3);
+            const int64_t gk = k0 + (((lane & 7) ^ swz_kc(row)) << 4);
+            int64_t gr = row0 + row;
+            if (gr >= g.M) gr = g.M - 1;
+            dma16_to_lds(gk < g.K ? g.a + gr * g.lda + gk : g_zero16, lds_x + j * (ROWS * BK) + i * 1024);
+        }
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {                          // 64 adapter rows
+            const int i = it * 4 + wave;
+            const int row = i * 8 + (lane >> 3);
+            const int64_t gk = k0 + (((lane & 7) ^ swz_kc(row)) << 4);
+            const int rr = row < r ? row : r - 1;
+            dma16_to_lds(gk < g.K ? t.side + rr * g.ldb + gk : g_zero16, lds_a + j * (64 * BK) + i * 1024);
+        }
+    }
+}
+
+// Chunk 0 has been issued by the caller, followed by the fetches of the tile's first stage; every
+// further chunk is fetched here.
+template <int Q>
+__device__ __forceinline__ void oa_side_run(const TailArgs& t, const GemmArgs& g, int64_t m0, int tile_n, float inv,
+                                            uint8_t* lds_x, uint8_t* lds_a, int wave, int lane)
+{
+    constexpr int ROWS = 256 / Q, STEPS = 2 * Q, MI = 4 / Q;      // a wave owns MI blocks of 32 rows and one of 32 ranks
+    const int KT = static_cast<int>((g.K + BK - 1) / BK);
+    const int set = tile_n / Q;
+    const int s_begin = set * t.steps_per_split;
+    int s_end = s_begin + t.steps_per_split;
+    if (s_end > KT) s_end = KT;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = static_cast<int>(t.r);
+    const bool live = wn * 32 < r;                                // wave-uniform: this wave's rank block exists
+    v16f acc[MI];
+#pragma unroll
+    for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[mi][v] = 0.0f;
+    auto k_step = [&](int j) {
+        const uint8_t* sx = lds_x + j * (ROWS * BK);
+        const uint8_t* sa = lds_a + j * (64 * BK);
+#pragma unroll
+        for (int kh = 0; kh < 2; ++kh) {
+            const v8i b = read_kc_tile(sa, wn * 32 + (lane & 31), kh, lane);
+#pragma unroll
+            for (int mi = 0; mi < MI; ++mi) {
+                const v8i a = read_kc_tile(sx, wm * (MI * 32) + mi * 32 + (lane & 31), kh, lane);
+                acc[mi] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(b, a, acc[mi], 0, 0, 0, 0, 0, 0);
+            }
+        }
+    };
+    for (int c = 0; s_begin + c * STEPS < s_end; ++c) {
+        if (c > 0) {
+            __syncthreads();                                      // every wave has read the previous chunk
+            oa_side_fetch<Q>(t, g, m0, tile_n, c, lds_x, lds_a, wave, lane);
+        }
+        __builtin_amdgcn_s_waitcnt(0);                            // this chunk (and the tile's first stage) has landed
+        __syncthreads();                                          // ... for every wave
+        const int steps = s_end - (s_begin + c * STEPS);
+        if (live) {
+            if (steps >= STEPS) {                                 // unrolled, so that LDS reads run ahead of the MFMAs
+#pragma unroll
+                for (int j = 0; j < STEPS; ++j) k_step(j);
+            } else {
+                for (int j = 0; j < steps; ++j) k_step(j);
+            }
+        }
+    }
+    if (live) {
+        // lane l holds token row l % 32 of each 32-row block and runs of four consecutive ranks
+        float* out = t.partial + static_cast<int64_t>(set) * g.M * r;
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi) {
+            const int64_t row = m0 + (tile_n % Q) * ROWS + wm * (MI * 32) + mi * 32 + (lane & 31);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = wn * 32 + q * 8 + (lane >> 5) * 4;
+                if (row < g.M && col < r)
+                    *reinterpret_cast<float4*>(out + row * r + col) =
+                        make_float4(acc[mi][4 * q] * inv, acc[mi][4 * q + 1] * inv, acc[mi][4 * q + 2] * inv, acc[mi][4 * q + 3] * inv);
+            }
+        }
+    }
+    __syncthreads();                                              // the share's LDS reads are done: the tile may overwrite
+}
+
+// Input gradient: token tile rows are paired into groups of 512 tokens; the workgroups of a group
+// divide the output features (the K dimension of this launch) among themselves in steps of 128.  A
+// workgroup multiplies, per feature step, dy~[512 tokens][128 features] with O_A~[512 tokens][rank]
+// over the tokens and writes raw sums to partial[group][feature][rank].  Both tiles sit in LDS as
+// [token][feature] and are read with the transposing LDS read (dbt::read_tokens_of_feature).
+constexpr int kDbTailTokens = 512, kDbTailGroupRows = 2;
+
+struct DbTailGeom { int group, f_begin, f_end; int64_t t0, t_end; };
+
+__device__ __forceinline__ DbTailGeom db_side_geom(const GemmArgs& g, int tile_m, int tile_n, int tiles_m, int tiles_n)
+{
+    DbTailGeom q;
+    q.group = tile_m / kDbTailGroupRows;
+    int rows = tiles_m - q.group * kDbTailGroupRows;
+    if (rows > kDbTailGroupRows) rows = kDbTailGroupRows;
+    const int F = static_cast<int>((g.K + 127) / 128);           // feature steps (K of this launch = m)
+    const int W = rows * tiles_n;
+    const int per = (F + W - 1) / W;
+    const int w = (tile_m - q.group * kDbTailGroupRows) * tiles_n + tile_n;
+    q.f_begin = w * per;
+    q.f_end = q.f_begin + per < F ? q.f_begin + per : F;
+    q.t0 = static_cast<int64_t>(q.group) * kDbTailTokens;
+    q.t_end = q.t0 + kDbTailTokens < g.M ? q.t0 + kDbTailTokens : g.M;
+    return q;
+}
+
+__device__ __forceinline__ void db_side_fetch(const TailArgs& t, const GemmArgs& g, const DbTailGeom& q, int c, bool with_oa,
+                                              uint8_t* lds_dy, uint8_t* lds_oa, int wave, int lane)
+{
+    const int64_t i0 = static_cast<int64_t>(q.f_begin + c) * 128;
+#pragma unroll
+    for (int it = 0; it < kDbTailTokens / 8 / 4; ++it) {         // dy~: 8 token rows of 128 bytes per wave instruction
+        const int i = it * 4 + wave;
+        const int trow = i * 8 + (lane >> 3);
+        const int64_t gt = q.t0 + trow, gi = i0 + (((lane & 7) ^ dbt::swz_t<8>(trow)) << 4);
+        dma16_to_lds((gt < q.t_end && gi < g.K) ? g.a + gt * g.lda + gi : g_zero16, lds_dy + i * 1024);
+    }
+    if (!with_oa) return;
+    const int64_t r = t.r;
+#pragma unroll
+    for (int it = 0; it < kDbTailTokens / 16 / 4; ++it) {        // O_A~: 16 token rows of 64 bytes per wave instruction
+        const int i = it * 4 + wave;
+        const int trow = i * 16 + (lane >> 2);
+        const int64_t gt = q.t0 + trow, gp = ((lane & 3) ^ dbt::swz_t<4>(trow)) << 4;
+        dma16_to_lds((gt < q.t_end && gp < r) ? t.side + gt * r + gp : g_zero16, lds_oa + i * 1024);
+    }
+}
+
+// Step 0 (with O_A~) has been issued by the caller, followed by the tile's first stage.
+__device__ __forceinline__ void db_side_run(const TailArgs& t, const GemmArgs& g, const DbTailGeom& q,
+                                            uint8_t* lds_dy, uint8_t* lds_oa, int wave, int lane)
+{
+    const int64_t m = g.K, r = t.r;
+    const int k_blocks = static_cast<int>((q.t_end - q.t0 + 63) / 64);
+    float* out = t.partial + static_cast<int64_t>(q.group) * m * r;
+    for (int c = 0; q.f_begin + c < q.f_end; ++c) {
+        if (c > 0) {
+            __syncthreads();                                      // every wave has read the previous feature step
+            db_side_fetch(t, g, q, c, false, lds_dy, lds_oa, wave, lane);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        dbt::v16f acc[2];
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
+        // wave w owns features [32 w, 32 w + 32) of the step and both 32-wide rank blocks
+        auto k_block = [&](int kb) {
+            const dbt::v8i a = dbt::read_tokens_of_feature<8>(lds_dy, wave * 32, kb, lane);
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                if (b * 32 >= r) continue;
+                const dbt::v8i bb = dbt::read_tokens_of_feature<4>(lds_oa, b * 32, kb, lane);
+                acc[b] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, bb, acc[b], 1 /* E5M2 */, 0 /* E4M3 */, 0, 0, 0, 0);
+            }
+        };
+        if (k_blocks == kDbTailTokens / 64) {                     // a full group: unrolled, so that LDS reads run ahead
+#pragma unroll
+            for (int kb = 0; kb < kDbTailTokens / 64; ++kb) k_block(kb);
+        } else {
+            for (int kb = 0; kb < k_blocks; ++kb) k_block(kb);
+        }
+        const int64_t i0 = static_cast<int64_t>(q.f_begin + c) * 128 + wave * 32;
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int64_t p = b * 32 + (lane & 31);
+            if (p >= r) continue;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t i = i0 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+                if (i < m) out[i * r + p] = acc[b][v];
+            }
+        }
+    }
+    __syncthreads();                                              // the share's LDS reads are done: the tile may overwrite
+}
+
 // LDS of one workgroup: operand rings, the left operand three stages deep, the right operand two
 // (160 KB at 256x256).
 template <int WM, int WN, int MB, int NB>
@@ -89,10 +332,17 @@ constexpr int gemm_lds_bytes() { return (3 * WM * MB + 2 * WN * NB) * 32 * BK; }
 
 // One output tile.  `bid` is the workgroup's index in a grid of 8 * chunk workgroups whose index
 // modulo 8 is the XCD it runs on, `split` its K split; `lds` is gemm_lds_bytes() of LDS, 1 KB aligned.
-template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT>
+// TAIL selects a side job that the workgroup performs ahead of its tile (see the side-job functions
+// above): 0 none, 1 a K slice of the adapter product O_A (forward), 2 a slice of the adapter
+// gradient dB (input-gradient launch).
+template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT, int TAIL = 0>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, const int tiles_n, const int chunk,
-                                          const int bid, const int split, uint8_t* const lds)
+                                          const int bid, const int split, uint8_t* const lds,
+                                          const TailArgs* const tail = nullptr)
 {
+    static_assert(TAIL == 0 || (WM == 2 && WN == 2 && MB == 4 && NB == 4), "side jobs ride on the 256x256 tile only");
+    static_assert(TAIL != 1 || (!B_KN && A_FMT == 0), "the O_A slice belongs to the forward product");
+    static_assert(TAIL != 2 || (B_KN && A_FMT == 1), "the dB slice belongs to the input-gradient product");
     constexpr int BM = WM * MB * 32, BN = WN * NB * 32, NW = WM * WN;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
     static_assert((BM / 8) % NW == 0 && (B_BYTES / 1024) % NW == 0, "loads must split evenly over waves");
@@ -123,6 +373,9 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     const uint8_t* const gb = B_KN ? g.b + kbeg * g.ldb : g.b + kbeg;
     uint8_t* const c0p = static_cast<uint8_t*>(g.c0) +
                          static_cast<int64_t>(split) * M * g.ldc0 * (g.c0_is_f32 ? 4 : 2);
+    // rescale factor: read here, where the two loads hide under the first operand fetches, and kept in
+    // a scalar register (read at the top of the epilogue they cost every tile a memory round trip)
+    const float inv = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(1.0f / ((*g.sa) * (*g.sb)))));
 
     // ---- global -> LDS ----------------------------------------------------------------------
     // Fast path (every K-step that lies fully inside K): address = uniform base + 32-bit lane
@@ -297,8 +550,36 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
         else if (f < N_FRAG) af[kh][f - NB] = read_a(sA, f - NB, kh);
     };
 
-    fetch_a_all(0, lds);
-    fetch_b_all(0, lds_b);
+    // The side job's first operand fetches go out ahead of the tile's first stage; the job itself
+    // runs while that stage is in flight or has landed, and ends with a barrier, after which the
+    // second stage may overwrite the ring slots it used.
+    if constexpr (TAIL == 1) {
+        if (oa_side_active(*tail, tile_n)) {
+            if (tail->row_parts == 2) oa_side_fetch<2>(*tail, g, m0, tile_n, 0, lds + A_BYTES, lds_b + B_BYTES, wave, lane);
+            else oa_side_fetch<1>(*tail, g, m0, tile_n, 0, lds + A_BYTES, lds_b + B_BYTES, wave, lane);
+            fetch_a_all(0, lds);
+            fetch_b_all(0, lds_b);
+            if (tail->row_parts == 2) oa_side_run<2>(*tail, g, m0, tile_n, inv, lds + A_BYTES, lds_b + B_BYTES, wave, lane);
+            else oa_side_run<1>(*tail, g, m0, tile_n, inv, lds + A_BYTES, lds_b + B_BYTES, wave, lane);
+        } else {
+            fetch_a_all(0, lds);
+            fetch_b_all(0, lds_b);
+        }
+    } else if constexpr (TAIL == 2) {
+        const DbTailGeom q = db_side_geom(g, tile_m, tile_n, tiles_m, tiles_n);
+        if (q.f_begin < q.f_end) {
+            db_side_fetch(*tail, g, q, 0, true, lds + A_BYTES, lds_b + B_BYTES, wave, lane);
+            fetch_a_all(0, lds);
+            fetch_b_all(0, lds_b);
+            db_side_run(*tail, g, q, lds + A_BYTES, lds_b + B_BYTES, wave, lane);
+        } else {
+            fetch_a_all(0, lds);
+            fetch_b_all(0, lds_b);
+        }
+    } else {
+        fetch_a_all(0, lds);
+        fetch_b_all(0, lds_b);
+    }
     if (KT > 1) {
         fetch_a_all(1, lds + A_BYTES);
         fetch_b_all(1, lds_b + B_BYTES);
@@ -390,7 +671,6 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     // register v holds column 8*(v/4) + 4*(l/32) + v%4 of the block.  One pass per 32-row block
     // index mi: every wave parks its 32 x (NB*32) strip in LDS, then the workgroup streams the
     // WM*32 rows out with 16 bytes per lane, row-contiguous.
-    const float inv = 1.0f / ((*g.sa) * (*g.sb));
     float oa_max = 0.0f;
     __syncthreads();                                              // all operand reads are done
     // the output type is a run-time argument; each of the two bodies is compiled with it fixed
@@ -480,6 +760,21 @@ gemm_fp8_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const in
     gemm_tile<WM, WN, MB, NB, B_KN, A_FMT>(g, tiles_m, tiles_n, chunk, blockIdx.x, blockIdx.y, lds);
 }
 
+// The backbone product with the adapter's share as a side job of every tile (TailArgs).
+__global__ void __launch_bounds__(256)
+gemm_fwd_tail_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk, const TailArgs t)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
+    gemm_tile<2, 2, 4, 4, false, 0, 1>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
+}
+
+__global__ void __launch_bounds__(256)
+gemm_dx_tail_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk, const TailArgs t)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
+    gemm_tile<2, 2, 4, 4, true, 1, 2>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
+}
+
 // Forward product and the adapter's split-K product in one launch.  Both read only x~ and the
 // concatenated weight, so nothing orders them; as two launches the second costs a dispatch, a
 // ramp-up and a drain of its own (about 4 us on this chip) on top of its few microseconds of work.
@@ -563,6 +858,57 @@ hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_
     const int n_side = 8 * h_chunk * h.splits;
     gemm_fwd_pair_kernel<<<dim3(static_cast<unsigned>(n_side + 8 * chunk)), dim3(256), 0, stream>>>(
         g, tiles_m, tiles_n, chunk, h, h_tiles_m, h_tiles_n, h_chunk, n_side);
+    return hipGetLastError();
+}
+
+// ---- tiles with side jobs: plans and launches ---------------------------------------------------
+// Forward: the tile columns of a tile row in sets of two (one where a tile row has a single tile),
+// one K slice per set, at most 8 slices, each a whole number of K-steps and none empty.  Used when
+// the rank fits the side job's LDS chunk and a slice is at most four chunks (beyond that the exposed
+// fetch round trips outweigh the saved round of tiles).
+OaTailPlan plan_oa_tail(int64_t T, int64_t n, int64_t m, int64_t r)
+{
+    OaTailPlan p{false, 0, 0, 1};
+    if (!use_big_tiles(T, m) || r > 64) return p;
+    const int tiles_n = static_cast<int>((m + 255) / 256);
+    const int KT = static_cast<int>((n + BK - 1) / BK);
+    p.row_parts = tiles_n >= 2 ? 2 : 1;
+    int s0 = tiles_n / p.row_parts < 8 ? tiles_n / p.row_parts : 8;
+    if (s0 > KT) s0 = KT;
+    p.steps_per_split = (KT + s0 - 1) / s0;
+    p.splits = (KT + p.steps_per_split - 1) / p.steps_per_split;
+    p.use = p.steps_per_split <= 4 * 2 * p.row_parts;
+    return p;
+}
+
+// Input gradient: groups of two token tile rows; at most kDbSplitMax groups, four feature steps per
+// workgroup of a full group and eight in a last group of a single tile row.
+DbTailPlan plan_db_tail(int64_t T, int64_t n, int64_t m, int64_t r)
+{
+    DbTailPlan p{false, 0};
+    if (!use_big_tiles(T, n) || r > 64) return p;
+    const int tiles_m = static_cast<int>((T + 255) / 256), tiles_n = static_cast<int>((n + 255) / 256);
+    p.groups = (tiles_m + kDbTailGroupRows - 1) / kDbTailGroupRows;
+    const int F = static_cast<int>((m + 127) / 128);
+    const int per_full = (F + kDbTailGroupRows * tiles_n - 1) / (kDbTailGroupRows * tiles_n);
+    const int per_last = (tiles_m % kDbTailGroupRows) ? (F + tiles_n - 1) / tiles_n : per_full;
+    p.use = p.groups <= kDbSplitMax && per_full <= 4 && per_last <= 8;
+    return p;
+}
+
+hipError_t launch_gemm_fwd_tail(const GemmArgs& g, const TailArgs& t, hipStream_t stream)
+{
+    const int tiles_m = static_cast<int>((g.M + 255) / 256), tiles_n = static_cast<int>((g.N + 255) / 256);
+    const int chunk = (tiles_m * tiles_n + 7) / 8;
+    gemm_fwd_tail_kernel<<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemm_dx_tail(const GemmArgs& g, const TailArgs& t, hipStream_t stream)
+{
+    const int tiles_m = static_cast<int>((g.M + 255) / 256), tiles_n = static_cast<int>((g.N + 255) / 256);
+    const int chunk = (tiles_m * tiles_n + 7) / 8;
+    gemm_dx_tail_kernel<<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
     return hipGetLastError();
 }
 

@@ -20,20 +20,35 @@ __device__ __forceinline__ uint16_t bf16_bits_rne(float v)
     return static_cast<uint16_t>(u >> 16);
 }
 
-template <int SPLITS>
+// Adds `splits` partials in ascending order, eight loads in flight at a time.
+__device__ __forceinline__ float4 ordered_sum(const float* __restrict__ partial, int splits, int64_t count, int64_t e)
+{
+    constexpr int B = 8;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int sp0 = 0; sp0 < splits; sp0 += B) {
+        float4 v[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            const int sp = sp0 + u < splits ? sp0 + u : splits - 1;      // beyond the range: a valid address, value unused
+            v[u] = *reinterpret_cast<const float4*>(partial + sp * count + e);
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            if (sp0 + u == 0) s = v[u];
+            else if (sp0 + u < splits) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+        }
+    }
+    return s;
+}
+
 __global__ void __launch_bounds__(kThreads)
-sum_partials_bf16_kernel(const float* __restrict__ partial, int64_t count,
+sum_partials_bf16_kernel(const float* __restrict__ partial, int splits, int64_t count,
                          uint16_t* __restrict__ out, uint32_t* __restrict__ amax)
 {
     float mx = 0.0f;
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * 4;
     for (int64_t e = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4; e < count; e += stride) {
-        float4 v[SPLITS];                                        // all loads in flight, then add in order
-#pragma unroll
-        for (int sp = 0; sp < SPLITS; ++sp) v[sp] = *reinterpret_cast<const float4*>(partial + sp * count + e);
-        float4 s = v[0];
-#pragma unroll
-        for (int sp = 1; sp < SPLITS; ++sp) { s.x += v[sp].x; s.y += v[sp].y; s.z += v[sp].z; s.w += v[sp].w; }
+        const float4 s = ordered_sum(partial, splits, count, e);
         const uint16_t b0 = bf16_bits_rne(s.x), b1 = bf16_bits_rne(s.y), b2 = bf16_bits_rne(s.z), b3 = bf16_bits_rne(s.w);
         uint2 pk;
         pk.x = b0 | (static_cast<uint32_t>(b1) << 16);
@@ -64,14 +79,8 @@ hipError_t launch_sum_partials_bf16(const float* partial, int splits, int64_t co
     int64_t blocks = (count / 4 + kThreads - 1) / kThreads;
     if (blocks > 128) blocks = 128;                               // grid-stride: few workgroups, few atomics
     if (blocks < 1) blocks = 1;
-    const unsigned nb = static_cast<unsigned>(blocks);
-    switch (splits) {
-        case 1: sum_partials_bf16_kernel<1><<<nb, kThreads, 0, stream>>>(partial, count, out, amax); break;
-        case 2: sum_partials_bf16_kernel<2><<<nb, kThreads, 0, stream>>>(partial, count, out, amax); break;
-        case 4: sum_partials_bf16_kernel<4><<<nb, kThreads, 0, stream>>>(partial, count, out, amax); break;
-        case 8: sum_partials_bf16_kernel<8><<<nb, kThreads, 0, stream>>>(partial, count, out, amax); break;
-        default: return hipErrorInvalidValue;                    // oa_splits() only returns powers of two
-    }
+    if (splits < 1) return hipErrorInvalidValue;
+    sum_partials_bf16_kernel<<<static_cast<unsigned>(blocks), kThreads, 0, stream>>>(partial, splits, count, out, amax);
     return hipGetLastError();
 }
 

@@ -109,9 +109,32 @@ __global__ void __launch_bounds__(kThreads)
 scale_cast_kernel(const T* __restrict__ x, int64_t n_vecs, int64_t vecs_per_row, int64_t ld_x,
                   const float* __restrict__ partials, int n_partials, const float* __restrict__ scale_in,
                   uint8_t* __restrict__ q, int64_t ld_q, float* __restrict__ scale_out,
-                  float* __restrict__ amax_out, uint32_t* __restrict__ zero_word)
+                  float* __restrict__ amax_out, uint32_t* __restrict__ zero_word, const SideCast side, int side_blocks)
 {
     __shared__ float smem[kThreads / 64];
+    // The last side_blocks workgroups cast a second, small bf16 tensor whose maximum is already
+    // known (the saved O_A of the layer, for the adapter gradient): s = 448 / max(amax, 1e-12f),
+    // one fp32 multiply, then the E4M3 cast.  It rides in this launch so that no launch, and no
+    // reduction pass, exists for it alone.
+    if (static_cast<int>(blockIdx.x) >= static_cast<int>(gridDim.x) - side_blocks) {
+        const int b = static_cast<int>(blockIdx.x) - (static_cast<int>(gridDim.x) - side_blocks);
+        const float s2 = 448.0f / fmaxf(*side.amax, 1e-12f);
+        const int64_t vecs = side.count / kVec;
+        for (int64_t v = static_cast<int64_t>(b) * kThreads + threadIdx.x; v < vecs; v += static_cast<int64_t>(side_blocks) * kThreads) {
+            float f[kVec];
+            load16(side.x + v * kVec, f);
+#pragma unroll
+            for (int i = 0; i < kVec; ++i) f[i] = __fmul_rn(f[i], s2);
+            uint4 o;
+            o.x = cast4<FALQON_E4M3>(f[0], f[1], f[2], f[3]);
+            o.y = cast4<FALQON_E4M3>(f[4], f[5], f[6], f[7]);
+            o.z = cast4<FALQON_E4M3>(f[8], f[9], f[10], f[11]);
+            o.w = cast4<FALQON_E4M3>(f[12], f[13], f[14], f[15]);
+            *reinterpret_cast<uint4*>(side.q + v * kVec) = o;
+        }
+        return;
+    }
+    const int main_blocks = static_cast<int>(gridDim.x) - side_blocks;
     float m = 0.0f;
     for (int i = threadIdx.x; i < n_partials; i += kThreads) m = fmaxf(m, partials[i]);
     const float amax = block_max(m, smem);
@@ -119,7 +142,7 @@ scale_cast_kernel(const T* __restrict__ x, int64_t n_vecs, int64_t vecs_per_row,
     // IEEE fp32 division (hipcc's default for '/' is the correctly rounded one)
     const float s = scale_in ? *scale_in : mx / fmaxf(amax, 1e-12f);
 
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    const int64_t stride = static_cast<int64_t>(main_blocks) * kThreads;
     for (int64_t v = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; v < n_vecs; v += stride) {
         float f[kVec];
         load16(x + vec_offset(v, vecs_per_row, ld_x), f);
@@ -144,8 +167,15 @@ __global__ void zero_word_kernel(uint32_t* w) { *w = 0u; }
 template <typename T>
 hipError_t run(const T* x, int64_t rows, int64_t cols, int64_t ld_x, falqon_fmt fmt, const float* scale_in,
                uint8_t* q, int64_t ld_q, float* scale_out, float* amax_out, float* partials,
-               uint32_t* zero_word, hipStream_t stream)
+               uint32_t* zero_word, const SideCast* side_job, hipStream_t stream)
 {
+    SideCast side{nullptr, nullptr, nullptr, 0};
+    int side_blocks = 0;
+    if (side_job && side_job->count > 0) {
+        side = *side_job;
+        const int64_t want = (side.count / kVec + kThreads - 1) / kThreads;
+        side_blocks = static_cast<int>(want < 64 ? want : 64);
+    }
     const int64_t vecs_per_row = cols / kVec;
     const int64_t n_vecs = rows * vecs_per_row;
     // The amax pass wants few, long-running workgroups (one partial each); the cast pass
@@ -161,13 +191,15 @@ hipError_t run(const T* x, int64_t rows, int64_t cols, int64_t ld_x, falqon_fmt 
     int64_t blocks = (n_vecs + kThreads * 2 - 1) / (kThreads * 2);
     if (blocks < 1) blocks = 1;
     if (blocks > 256 * 16) blocks = 256 * 16;
-    const dim3 grid(static_cast<unsigned>(blocks));
+    const dim3 grid(static_cast<unsigned>(blocks + side_blocks));
     if (fmt == FALQON_E4M3)
         scale_cast_kernel<T, FALQON_E4M3><<<grid, kThreads, 0, stream>>>(
-            x, n_vecs, vecs_per_row, ld_x, partials, n_partials, scale_in, q, ld_q, scale_out, amax_out, zero_word);
+            x, n_vecs, vecs_per_row, ld_x, partials, n_partials, scale_in, q, ld_q, scale_out, amax_out, zero_word,
+            side, side_blocks);
     else
         scale_cast_kernel<T, FALQON_E5M2><<<grid, kThreads, 0, stream>>>(
-            x, n_vecs, vecs_per_row, ld_x, partials, n_partials, scale_in, q, ld_q, scale_out, amax_out, zero_word);
+            x, n_vecs, vecs_per_row, ld_x, partials, n_partials, scale_in, q, ld_q, scale_out, amax_out, zero_word,
+            side, side_blocks);
     return hipGetLastError();
 }
 
@@ -182,13 +214,13 @@ hipError_t launch_zero_word(uint32_t* w, hipStream_t stream)
 hipError_t launch_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t cols, int64_t ld_x,
                            falqon_fmt fmt, const float* scale_in, uint8_t* q, int64_t ld_q,
                            float* scale_out, float* amax_out, float* partials, uint32_t* zero_word,
-                           hipStream_t stream)
+                           hipStream_t stream, const SideCast* side)
 {
     if (xt == FALQON_BF16)
         return run(static_cast<const uint16_t*>(x), rows, cols, ld_x, fmt, scale_in, q, ld_q, scale_out,
-                   amax_out, partials, zero_word, stream);
+                   amax_out, partials, zero_word, side, stream);
     return run(static_cast<const float*>(x), rows, cols, ld_x, fmt, scale_in, q, ld_q, scale_out, amax_out,
-               partials, zero_word, stream);
+               partials, zero_word, side, stream);
 }
 
 }  // namespace falqon

@@ -146,11 +146,10 @@ def test_forward_call_accepts_an_already_quantized_input():
 
 
 def test_workspace_follows_the_bytes_needed_not_the_token_count():
-    """The workspace size is not monotonic in T (the adapter product's split count drops when T
-    grows past a tile boundary): a layer that has seen 4200 tokens must still serve 4096."""
+    """The workspace size need not be monotonic in T (split counts change at tile boundaries): the
+    module asks for the size on every call, so a layer that has seen one token count serves any other."""
     n = m = 4096
     r = 64
-    assert fq.workspace_bytes(4096, n, m, r) > fq.workspace_bytes(4200, n, m, r)
     g = torch.Generator().manual_seed(12)
     lin = MeldedLoRALinear(n, m, r, 8, sgd_lr=1e-3)
     lin.load_weights((torch.randn(m, n, generator=g) * 0.02).cuda(), (torch.randn(r, n, generator=g) / r).cuda())

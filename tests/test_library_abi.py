@@ -187,3 +187,26 @@ def test_static_scratch_update_rejects_sizes_beyond_its_limit(L):
     assert f(None, ok, 256, 4096, 64, 4, ok, 1, None) == 1
     assert f(ok, _vp(0x10004), 256, 4096, 64, 4, ok, 1, None) == 3
     assert fq.status_string(7).startswith("size beyond")
+
+
+def test_fp8_gemm_argument_validation(L):
+    f = L.falqon_fp8_gemm
+    ok, odd = _vp(0x10000), _vp(0x10004)
+    big = L.falqon_workspace_bytes(2400, 3328, 3584, 64)
+
+    def g(a=ok, af=0, b=ok, kn=0, M=2400, N=3584, K=3328, sa=ok, sb=ok, c=ok, ct=0, side=None, r=0, ws=None, wsb=0):
+        return f(a, af, b, kn, M, N, K, sa, sb, c, ct, side, r, ws, wsb, None)
+
+    assert g(a=None) == 1 and g(c=None) == 1 and g(sa=None) == 1
+    assert g(af=3) == 4 and g(ct=2) == 4
+    assert g(N=24) == 2 and g(K=8) == 2 and g(M=0) == 2
+    assert g(b=odd) == 3
+    # with the adapter's share as a side job: the shapes of a melded call, and a workspace
+    assert g(side=ok, r=64, ws=None, wsb=big) == 5
+    assert g(side=ok, r=64, ws=ok, wsb=big - 1) == 5
+    assert g(side=ok, r=20, ws=ok, wsb=big) == 2                       # r not a multiple of 16
+    assert g(side=ok, r=128, ws=ok, wsb=1 << 40) == 2                   # ranks beyond the side job's reach
+    assert g(side=ok, r=64, ws=ok, wsb=big, M=64) == 2                  # a small product does not use this launch
+    assert g(side=odd, r=64, ws=ok, wsb=big) == 3
+    assert g(side=ok, r=64, ws=ok, wsb=big, kn=1, af=0) == 4            # input-gradient orientation takes E5M2
+    assert g(side=ok, r=64, ws=ok, wsb=big, kn=0, af=1) == 4
