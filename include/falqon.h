@@ -130,6 +130,8 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
  *   d_b       = dyq^T . oaq / (s_dy * s_oa)          modified LoRA-backward equation
  *   delta_buf += -lr * d_b                           if delta_buf != NULL (plain SGD as
  *                                                    the optimizer that fills the buffer)
+ *   row_scores_i = sum_p |delta_buf[i,p]|            if row_scores != NULL: the first line of
+ *                                                    falqon_proxy_update, on the buffer this step leaves
  *
  *   dy         in   bf16 [T, m]
  *   o_a, amax_oa in bf16 [T, r] and device scalar, as falqon_melded_fwd produced them
@@ -138,13 +140,20 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
  *                   input needs no gradient, such as the first projections behind a frozen embedding)
  *   d_b        out  fp32 [m, r]
  *   delta_buf  i/o  nullable fp32 [m, r]
+ *   row_scores out  nullable (needs delta_buf); falqon_row_score_bytes(m) bytes, 8-byte aligned.  The
+ *                   kernel that writes the buffer has its rows at hand, so it can leave their scores
+ *                   for a falqon_proxy_update that follows with the buffer unchanged (one launch less).
+ *                   The array's content beyond "valid input of falqon_proxy_update" is internal.
  */
 falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* s_w,
                                 const void* o_a, const float* amax_oa,
                                 int64_t T, int64_t n, int64_t m, int64_t r,
                                 uint8_t* dyq, float* s_dy, void* dx, falqon_dtype dxt,
-                                float* d_b, float* delta_buf, float lr,
+                                float* d_b, float* delta_buf, float lr, double* row_scores,
                                 void* ws, size_t ws_bytes, void* stream);
+
+/* Bytes of a row-score array for m buffer rows (host function); 0 if m is out of range. */
+size_t falqon_row_score_bytes(int64_t m);
 
 /*
  * Row-wise proxy update (update equation; last two lines of the backward-and-update loop):
@@ -163,17 +172,22 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
  *   delta_buf  i/o  fp32 [m, r]
  *   wq         i/o  E4M3 [(m+r), n]
  *   idx_out    out  int32 [k], device
+ *   row_scores in   nullable: the array falqon_melded_bwd filled for this very buffer content; the
+ *                   scores are then not formed again.  The caller vouches that the buffer has not
+ *                   changed since (another backward step, an optimizer step or an update makes the
+ *                   array stale); NULL is always correct.
  */
 falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
-                                  int32_t* idx_out, int clear_selected,
+                                  int32_t* idx_out, int clear_selected, const double* row_scores,
                                   void* ws, size_t ws_bytes, void* stream);
 
 /*
  * falqon_proxy_update for callers that cannot allocate device memory and so have no workspace to
  * pass: code under HIP graph capture, tight loops, harnesses that forbid hipMalloc.  Same
- * arguments, same kernels and bit-identical results; the scratch (row scores and the staged rows
- * of the selection) lives in a static device array of the library, 384 KiB per GPU, held until the
- * process ends.  The call allocates and frees nothing.
+ * arguments (the scores are always formed here), same kernels and bit-identical results; the
+ * scratch (row scores with their block maxima, and the staged rows of the selection) lives in a
+ * static device array of the library, 386 KiB per GPU, held until the process ends.  The call
+ * allocates and frees nothing.
  *
  * Limits: m <= 16384 and k * r <= 65536, else FALQON_ERR_LIMIT and nothing is launched.
  * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two

@@ -51,9 +51,11 @@ def lib():
                                         vp, c.c_size_t, vp]
         L.falqon_melded_bwd.restype = c.c_int
         L.falqon_melded_bwd.argtypes = [vp, vp, f32p, vp, f32p, i64, i64, i64, i64, vp, f32p, vp, c.c_int,
-                                        f32p, f32p, c.c_float, vp, c.c_size_t, vp]
+                                        f32p, f32p, c.c_float, vp, vp, c.c_size_t, vp]
+        L.falqon_row_score_bytes.restype = c.c_size_t
+        L.falqon_row_score_bytes.argtypes = [i64]
         L.falqon_proxy_update.restype = c.c_int
-        L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, c.c_size_t, vp]
+        L.falqon_proxy_update.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp, vp, c.c_size_t, vp]
         L.falqon_proxy_update_static.restype = c.c_int
         L.falqon_proxy_update_static.argtypes = [f32p, vp, i64, i64, i64, i64, vp, c.c_int, vp]
         L.falqon_db_bf16.restype = c.c_int
@@ -141,21 +143,30 @@ def melded_fwd(x, wq, s_w, m: int, r: int, xq, s_x, y, o_a, amax_oa, ws) -> None
     _check(st, "falqon_melded_fwd")
 
 
-def melded_bwd(dy, wq, s_w, o_a, amax_oa, n: int, r: int, dyq, s_dy, dx, d_b, delta_buf, lr: float, ws) -> None:
-    """dx = None: the input-gradient product is skipped.  delta_buf = None: no buffer step."""
-    _dev(dy, wq, s_w, o_a, amax_oa, dyq, s_dy, dx, d_b, delta_buf, ws)
+def row_score_bytes(m: int) -> int:
+    return int(lib().falqon_row_score_bytes(m))
+
+
+def melded_bwd(dy, wq, s_w, o_a, amax_oa, n: int, r: int, dyq, s_dy, dx, d_b, delta_buf, lr: float, ws,
+               row_scores=None) -> None:
+    """dx = None: the input-gradient product is skipped.  delta_buf = None: no buffer step.
+    row_scores (uint8/float64 tensor of row_score_bytes(m) bytes): left for a proxy_update that follows."""
+    _dev(dy, wq, s_w, o_a, amax_oa, dyq, s_dy, dx, d_b, delta_buf, ws, row_scores)
     T, m = dy.shape
     st = lib().falqon_melded_bwd(_p(dy), _p(wq), _p(s_w), _p(o_a), _p(amax_oa), T, n, m, r, _p(dyq), _p(s_dy),
                                  _p(dx), _dtype_code(dx) if dx is not None else BF16, _p(d_b), _p(delta_buf), float(lr),
+                                 _p(row_scores),
                                  _p(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_melded_bwd")
 
 
-def proxy_update(delta_buf, wq, m: int, r: int, k: int, idx_out, ws, clear_selected: bool = True) -> None:
-    _dev(delta_buf, wq, idx_out, ws)
+def proxy_update(delta_buf, wq, m: int, r: int, k: int, idx_out, ws, clear_selected: bool = True,
+                 row_scores=None) -> None:
+    """row_scores: the array melded_bwd filled for this very buffer content (else the scores are formed here)."""
+    _dev(delta_buf, wq, idx_out, ws, row_scores)
     n = wq.shape[1]
     st = lib().falqon_proxy_update(_p(delta_buf), _p(wq), n, m, r, k, _p(idx_out), 1 if clear_selected else 0,
-                                   _p(ws), ws.numel() * ws.element_size(), _stream())
+                                   _p(row_scores), _p(ws), ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_proxy_update")
 
 
@@ -256,6 +267,8 @@ class MeldedLinear:
         self.amax_oa = torch.zeros(1, dtype=f32, device=dev)
         self.d_b = torch.empty(m, r, dtype=f32, device=dev)
         self.idx = torch.zeros(k, dtype=torch.int32, device=dev)
+        self.row_scores = torch.empty(row_score_bytes(m) // 8, dtype=torch.float64, device=dev)
+        self._scores_fresh = False      # row_scores describe delta_buf as it is now
         o = share_transients_with
         if o is not None:
             if (o.T, o.n, o.m, o.r) != (T, n, m, r) or o.y.dtype != out_dtype:
@@ -285,8 +298,11 @@ class MeldedLinear:
         return self.y
 
     def backward(self, dy: torch.Tensor, lr: float = 2e-4, accumulate: bool = True) -> torch.Tensor:
+        """With the buffer step the call also leaves the buffer's row scores for the update that follows."""
         melded_bwd(dy, self.wq, self.s_w, self.o_a, self.amax_oa, self.n, self.r, self.dyq, self.s_dy, self.dx,
-                   self.d_b, self.delta_buf if accumulate else None, lr, self.ws)
+                   self.d_b, self.delta_buf if accumulate else None, lr, self.ws,
+                   row_scores=self.row_scores if accumulate else None)
+        self._scores_fresh = accumulate
         return self.dx
 
     def adamw_step(self, step: int, sum_sq: Optional[torch.Tensor] = None, lr: float = 2e-4, beta1: float = 0.9,
@@ -297,7 +313,14 @@ class MeldedLinear:
             self.exp_avg_sq = torch.zeros_like(self.d_b)
         adamw_delta(self.d_b, self.exp_avg, self.exp_avg_sq, self.delta_buf, step, lr, beta1, beta2, eps, sum_sq,
                     max_norm)
+        self._scores_fresh = False
 
-    def update(self, clear_selected: bool = True) -> torch.Tensor:
-        proxy_update(self.delta_buf, self.wq, self.m, self.r, self.k, self.idx, self.ws, clear_selected)
+    def update(self, clear_selected: bool = True, reuse_scores: bool = False) -> torch.Tensor:
+        """reuse_scores: take the row scores the last backward() left instead of forming them again.  Only
+        the caller knows whether delta_buf was written in between (this class sees its own calls only), so
+        it has to ask for it; it is honoured only directly after a backward() with the buffer step."""
+        scores = self.row_scores if (reuse_scores and self._scores_fresh) else None
+        proxy_update(self.delta_buf, self.wq, self.m, self.r, self.k, self.idx, self.ws, clear_selected,
+                     row_scores=scores)
+        self._scores_fresh = False
         return self.idx

@@ -14,6 +14,7 @@
 // each split writes an fp32 partial and a second pass adds the partials in a fixed order
 // (bitwise reproducible, no floating-point atomics) and applies the proxy-buffer step.
 #include "db_tile.h"
+#include "row_scores.h"
 
 namespace falqon {
 namespace {
@@ -38,41 +39,70 @@ __device__ __forceinline__ float buffer_step(float buf, float lr, float g)
     return buf + step;
 }
 
-// dB = (sum of partials, split ascending) / (s_dy * s_oa);  delta_buf += -lr * dB
+// dB = (sum of partials, split ascending) / (s_dy * s_oa);  delta_buf += -lr * dB.
+// A workgroup owns 64 rows of dB.  With `score` set (only together with delta_buf) it keeps the new
+// buffer rows in LDS and leaves their L1 norms and the block's largest norm for the proxy update.
 __global__ void __launch_bounds__(kThreads)
-db_reduce_kernel(const float* __restrict__ partial, int splits, int64_t count,
+db_reduce_kernel(const float* __restrict__ partial, int splits, int64_t m, int r,
                  const float* __restrict__ s_dy, const float* __restrict__ amax_oa,
-                 float* __restrict__ d_b, float* delta_buf, float lr)
+                 float* __restrict__ d_b, float* delta_buf, float lr, double* __restrict__ score)
 {
+    extern __shared__ float s_rows[];                                              // 64 x (r + 4) floats when score is set
     const float s_oa_scale = amax_oa ? 448.0f / fmaxf(*amax_oa, 1e-12f) : 1.0f;    // no amax: O_A was not cast
     const float inv = 1.0f / ((*s_dy) * s_oa_scale);
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads * 4;
-    for (int64_t e = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4; e < count; e += stride) {
-        constexpr int B = 8;                                          // loads in flight per batch
-        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int64_t count = m * r;
+    const int64_t row0 = static_cast<int64_t>(blockIdx.x) * kScoreRows;
+    const int64_t e0 = row0 * r;
+    int64_t e_end = e0 + static_cast<int64_t>(kScoreRows) * r;
+    if (e_end > count) e_end = count;
+    const int r4 = r / 4, pitch = r + 4;
+    constexpr int B = 8, U = 4;                                    // splits per batch, float4 positions per thread and pass
+    for (int64_t base = e0 + threadIdx.x * 4; base < e_end; base += static_cast<int64_t>(U) * kThreads * 4) {
+        float4 s[U];
         for (int sp0 = 0; sp0 < splits; sp0 += B) {
-            float4 v[B];
+            float4 v[U][B];
 #pragma unroll
-            for (int u = 0; u < B; ++u) {
-                const int sp = sp0 + u < splits ? sp0 + u : splits - 1;  // beyond the range: a valid address, value unused
-                v[u] = *reinterpret_cast<const float4*>(partial + sp * count + e);
+            for (int u = 0; u < U; ++u) {
+                const int64_t e = base + static_cast<int64_t>(u) * kThreads * 4;
+                const int64_t ee = e < e_end ? e : e0;                   // beyond the block: a valid address, value unused
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    const int sp = sp0 + b < splits ? sp0 + b : splits - 1;
+                    v[u][b] = *reinterpret_cast<const float4*>(partial + sp * count + ee);
+                }
             }
 #pragma unroll
-            for (int u = 0; u < B; ++u) {
-                if (sp0 + u == 0) s = v[u];
-                else if (sp0 + u < splits) { s.x += v[u].x; s.y += v[u].y; s.z += v[u].z; s.w += v[u].w; }
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int b = 0; b < B; ++b) {
+                    if (sp0 + b == 0) s[u] = v[u][b];
+                    else if (sp0 + b < splits) { s[u].x += v[u][b].x; s[u].y += v[u][b].y; s[u].z += v[u][b].z; s[u].w += v[u][b].w; }
+                }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = base + static_cast<int64_t>(u) * kThreads * 4;
+            if (e >= e_end) continue;
+            float4 g = s[u];
+            g.x *= inv; g.y *= inv; g.z *= inv; g.w *= inv;
+            *reinterpret_cast<float4*>(d_b + e) = g;
+            if (delta_buf) {
+                float4 d = *reinterpret_cast<const float4*>(delta_buf + e);
+                d.x = buffer_step(d.x, lr, g.x);
+                d.y = buffer_step(d.y, lr, g.y);
+                d.z = buffer_step(d.z, lr, g.z);
+                d.w = buffer_step(d.w, lr, g.w);
+                *reinterpret_cast<float4*>(delta_buf + e) = d;
+                if (score) {
+                    const int64_t q4 = (e - e0) / 4;
+                    *reinterpret_cast<float4*>(s_rows + (q4 / r4) * pitch + (q4 % r4) * 4) = d;
+                }
             }
         }
-        s.x *= inv; s.y *= inv; s.z *= inv; s.w *= inv;
-        *reinterpret_cast<float4*>(d_b + e) = s;
-        if (delta_buf) {
-            float4 d = *reinterpret_cast<const float4*>(delta_buf + e);
-            d.x = buffer_step(d.x, lr, s.x);
-            d.y = buffer_step(d.y, lr, s.y);
-            d.z = buffer_step(d.z, lr, s.z);
-            d.w = buffer_step(d.w, lr, s.w);
-            *reinterpret_cast<float4*>(delta_buf + e) = d;
-        }
+    }
+    if (score) {
+        __syncthreads();
+        score_rows_from_lds(s_rows, r, row0, m, score);
     }
 }
 
@@ -115,18 +145,18 @@ hipError_t launch_db_partial(const DbArgs& d, hipStream_t stream)
 }
 
 hipError_t launch_db_reduce(const DbArgs& d, const float* s_dy, float* d_b, float* delta_buf, float lr,
-                            hipStream_t stream)
+                            hipStream_t stream, double* score)
 {
-    const float* partials = d.partial;
-    const float* amax_oa = d.amax_oa;
-    const int splits = d.splits;
-    const int64_t m = d.m, r = d.r;
-    const int64_t count = m * r;
-    int64_t blocks = (count / 4 + kThreads - 1) / kThreads;
-    if (blocks < 1) blocks = 1;
-    if (splits < 1) return hipErrorInvalidValue;
-    db_reduce_kernel<<<static_cast<unsigned>(blocks), kThreads, 0, stream>>>(partials, splits, count, s_dy, amax_oa, d_b,
-                                                                          delta_buf, lr);
+    if (d.splits < 1) return hipErrorInvalidValue;
+    if (!delta_buf) score = nullptr;                              // the scores are those of the buffer the step leaves
+    const size_t lds = score ? sizeof(float) * kScoreRows * (static_cast<size_t>(d.r) + 4) : 0;
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&db_reduce_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+    }
+    db_reduce_kernel<<<static_cast<unsigned>(score_blocks(d.m)), kThreads, lds, stream>>>(
+        d.partial, d.splits, d.m, static_cast<int>(d.r), s_dy, d.amax_oa, d_b, delta_buf, lr, score);
     return hipGetLastError();
 }
 

@@ -3,6 +3,7 @@
 #include <cmath>
 
 #include "falqon_internal.h"
+#include "row_scores.h"
 
 namespace falqon {
 
@@ -19,7 +20,7 @@ WsLayout ws_layout(int64_t T, int64_t n, int64_t m, int64_t r)
     if (po.use && po.splits > oa_parts) oa_parts = po.splits;
     if (pd.use && pd.groups > db_parts) db_parts = pd.groups;
     w.amax_partials = off; off = align_up(off + sizeof(float) * kMaxAmaxBlocks, 256);
-    w.scores = off;        off = align_up(off + sizeof(double) * static_cast<size_t>(m), 256);
+    w.scores = off;        off = align_up(off + sizeof(double) * static_cast<size_t>(m + (m + 63) / 64), 256);
     w.delta_sel = off;     off = align_up(off + sizeof(float) * static_cast<size_t>(m) * static_cast<size_t>(r), 256);
     w.db_partials = off;   off = align_up(off + sizeof(float) * static_cast<size_t>(db_parts) *
                                                     static_cast<size_t>(m) * static_cast<size_t>(r), 256);
@@ -72,6 +73,12 @@ size_t falqon_workspace_bytes(int64_t T, int64_t n, int64_t m, int64_t r)
 {
     if (bad_layer_shape(T, n, m, r)) return 0;
     return ws_layout(T, n, m, r).total;
+}
+
+size_t falqon_row_score_bytes(int64_t m)
+{
+    if (m < 1 || m > 65536) return 0;
+    return sizeof(double) * static_cast<size_t>(m + score_blocks(m));
 }
 
 falqon_status falqon_quantize(const void* x, falqon_dtype xt, int64_t rows, int64_t cols, int64_t ld_x,
@@ -188,10 +195,12 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
                                 const void* o_a, const float* amax_oa,
                                 int64_t T, int64_t n, int64_t m, int64_t r,
                                 uint8_t* dyq, float* s_dy, void* dx, falqon_dtype dxt,
-                                float* d_b, float* delta_buf, float lr,
+                                float* d_b, float* delta_buf, float lr, double* row_scores,
                                 void* ws, size_t ws_bytes, void* stream)
 {
     if (dxt != FALQON_BF16 && dxt != FALQON_F32) return FALQON_ERR_ENUM;
+    if (row_scores && !delta_buf) return FALQON_ERR_NULL;
+    if (row_scores && (reinterpret_cast<uintptr_t>(row_scores) & 7u)) return FALQON_ERR_ALIGN;
     if (bad_layer_shape(T, n, m, r)) return FALQON_ERR_SHAPE;
     if (!dy || !wq || !s_w || !o_a || !amax_oa || !dyq || !s_dy || !d_b) return FALQON_ERR_NULL;   // dx may be NULL
     if (misaligned(dy) || misaligned(wq) || misaligned(o_a) || misaligned(dyq) || (dx && misaligned(dx)) ||
@@ -239,7 +248,7 @@ falqon_status falqon_melded_bwd(const void* dy, const uint8_t* wq, const float* 
         if (e == hipSuccess) e = launch_db_partial(d, st);
     }
     if (e != hipSuccess) return FALQON_ERR_HIP;
-    e = launch_db_reduce(d, s_dy, d_b, delta_buf, lr, st);
+    e = launch_db_reduce(d, s_dy, d_b, delta_buf, lr, st, row_scores);
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 
@@ -264,19 +273,20 @@ falqon_status falqon_db_bf16(const uint8_t* dyq, const float* s_dy, const void* 
 }
 
 falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
-                                  int32_t* idx_out, int clear_selected,
+                                  int32_t* idx_out, int clear_selected, const double* row_scores,
                                   void* ws, size_t ws_bytes, void* stream)
 {
     if (bad_layer_shape(1, n, m, r) || m > 65536 || k < 1 || k > m) return FALQON_ERR_SHAPE;
     if (!delta_buf || !wq || !idx_out) return FALQON_ERR_NULL;
-    if (misaligned(delta_buf) || misaligned(wq) || (reinterpret_cast<uintptr_t>(idx_out) & 3u))
+    if (misaligned(delta_buf) || misaligned(wq) || (reinterpret_cast<uintptr_t>(idx_out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(row_scores) & 7u))
         return FALQON_ERR_ALIGN;
     const WsLayout L = ws_layout(1, n, m, r);
     if (!ws || ws_bytes < L.db_partials) return FALQON_ERR_WORKSPACE;
     if (misaligned(ws)) return FALQON_ERR_ALIGN;
     uint8_t* w8 = static_cast<uint8_t*>(ws);
     hipError_t e = launch_proxy_update(delta_buf, wq, n, m, r, k, idx_out, clear_selected,
-                                       reinterpret_cast<double*>(w8 + L.scores),
+                                       reinterpret_cast<double*>(w8 + L.scores), row_scores,
                                        reinterpret_cast<float*>(w8 + L.delta_sel), static_cast<hipStream_t>(stream));
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }

@@ -16,7 +16,7 @@ constexpr int kDbSplitMax = 32;        // upper bound on the token splits of the
 
 struct WsLayout {
     size_t amax_partials;   // float[kMaxAmaxBlocks]
-    size_t scores;          // double[m]
+    size_t scores;          // double[m + ceil(m / 64)]: row scores of the proxy buffer and their block maxima
     size_t delta_sel;       // float[m][r]: buffer rows picked by the proxy update, in rank order
     size_t db_partials;     // float[splits][m][r]
     size_t oa_partials;     // float[splits][T][r]
@@ -95,8 +95,10 @@ struct DbArgs {
 DbArgs make_db_args(const uint8_t* dyq, const void* o_a, const float* amax_oa, int64_t T, int64_t m, int64_t r,
                     float* partials, int splits);
 hipError_t launch_db_partial(const DbArgs& d, hipStream_t stream);
+// score (nullable, used only with delta_buf): row scores of the buffer after the step, in the layout
+// of row_scores.h (m scores, then one maximum per block of 64 rows).
 hipError_t launch_db_reduce(const DbArgs& d, const float* s_dy, float* d_b, float* delta_buf, float lr,
-                            hipStream_t stream);
+                            hipStream_t stream, double* score = nullptr);
 // Variant with O_A kept in bf16 (db_wide.hip): d.amax_oa is not read and may be null, also in the reduce.
 hipError_t launch_db_wide_partial(const DbArgs& d, hipStream_t stream);
 // Input-gradient GEMM g ([K,N] right operand, E5M2 left operand, 256x256 tiles) and the partial pass
@@ -105,9 +107,12 @@ bool gemm_dx_db_pair_supported(const GemmArgs& g);
 hipError_t launch_gemm_dx_db_pair(const GemmArgs& g, const DbArgs& d, hipStream_t stream);
 
 // ---- proxy update (proxy.hip) ----------------------------------------------------------------
+// scores: scratch for m + ceil(m / 64) doubles (row_scores.h), written by the score pass; scores_in
+// (nullable): such an array already filled by the kernel that wrote the buffer, the score pass is
+// skipped.  delta_sel: scratch for k * r floats.
 hipError_t launch_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
-                               int32_t* idx_out, int clear_selected, double* scores, float* delta_sel,
-                               hipStream_t stream);
+                               int32_t* idx_out, int clear_selected, double* scores, const double* scores_in,
+                               float* delta_sel, hipStream_t stream);
 
 // The same update on the library's own static device scratch (no workspace, no allocation).
 constexpr int64_t kStaticMaxRows = 16384;          // m

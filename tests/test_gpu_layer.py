@@ -459,3 +459,39 @@ def test_accumulate_over_four_steps_then_one_update(shapes):
         assert np.array_equal(np_of(layer.idx), idx_ref)
         assert np.array_equal(np_of(layer.wq), w_ref)
         assert np_of(layer.delta_buf).tobytes() == buf_ref.tobytes()
+
+
+@pytest.mark.parametrize("shape", [(300, 512, 528, 32, 16), (2400, 3344, 3568, 64, 32), (64, 128, 4112, 48, 7), (200, 256, 272, 256, 5)])
+def test_backward_leaves_the_row_scores_for_the_update(shape):
+    """The buffer step can hand the buffer's row scores to the update that follows: the scores are the
+    oracle's bit for bit, every block maximum is the maximum of its 64 scores, and an update that
+    takes them does what an update that forms them does."""
+    T, n, m, r, k = shape
+    d, wcat, s_w = _inputs(T, n, m, r, True, seed=8100 + m)
+    g = np.random.default_rng(m)
+    buf0 = (g.normal(size=(m, r)) * 1e-3 * np.exp(g.normal(size=(m, 1)))).astype(np.float32)
+    buf0[5] = -buf0[9]                                                    # an exact tie between two rows
+    outs = []
+    for reuse in (True, False):
+        layer = layer_on_gpu(T, n, m, r, k, wcat, s_w, torch.bfloat16)
+        layer.delta_buf.copy_(torch.from_numpy(buf0))
+        layer.forward(d["x"].cuda())
+        layer.backward(d["dy"].cuda(), lr=0.05)
+        torch.cuda.synchronize()
+        buf = np_of(layer.delta_buf).copy()
+        sc = np_of(layer.row_scores)
+        assert sc[:m].tobytes() == oracle.row_scores(buf).tobytes()
+        blocks = [sc[b * 64: min(m, (b + 1) * 64)].max() for b in range((m + 63) // 64)]
+        assert np.array_equal(sc[m:], np.array(blocks))
+        layer.update(reuse_scores=reuse)
+        torch.cuda.synchronize()
+        idx_ref, w_ref, buf_ref = oracle.proxy_update(buf, wcat, m, r, k)
+        assert np.array_equal(np_of(layer.idx), idx_ref) and np.array_equal(np_of(layer.wq), w_ref)
+        assert np_of(layer.delta_buf).tobytes() == buf_ref.tobytes()
+        outs.append((np_of(layer.idx).copy(), np_of(layer.wq).copy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1])
+    # stale scores are never used by the layer object: a second update forms them again
+    layer.update(reuse_scores=True)
+    torch.cuda.synchronize()
+    idx_ref2, w_ref2, _ = oracle.proxy_update(buf_ref, w_ref, m, r, k)
+    assert np.array_equal(np_of(layer.idx), idx_ref2) and np.array_equal(np_of(layer.wq), w_ref2)

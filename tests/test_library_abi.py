@@ -82,13 +82,15 @@ def test_argument_validation_happens_before_any_launch(L):
 
     def bwd(**kw):
         a = dict(dy=ok, wq=ok, s_w=ok, o_a=ok, amax=ok, T=64, n=64, m=64, r=16, dyq=ok, s_dy=ok, dx=ok, dxt=0,
-                 d_b=ok, buf=ok, ws=ok, wsb=ws_bytes)
+                 d_b=ok, buf=ok, sc=None, ws=ok, wsb=ws_bytes)
         a.update(kw)
         return b(_vp(a["dy"]), _vp(a["wq"]), _vp(a["s_w"]), _vp(a["o_a"]), _vp(a["amax"]), a["T"], a["n"], a["m"],
                  a["r"], _vp(a["dyq"]), _vp(a["s_dy"]), _vp(a["dx"]), a["dxt"], _vp(a["d_b"]), _vp(a["buf"]),
-                 ctypes.c_float(1e-3), _vp(a["ws"]), a["wsb"], None)
+                 ctypes.c_float(1e-3), _vp(a["sc"]), _vp(a["ws"]), a["wsb"], None)
 
     assert bwd(dy=None) == 1 and bwd(d_b=None) == 1 and bwd(o_a=None) == 1
+    assert bwd(sc=ok, buf=None) == 1                                           # scores are those of the stepped buffer
+    assert bwd(sc=odd) == 3
     assert bwd(m=24) == 2 and bwd(T=-1) == 2
     assert bwd(dx=odd) == 3 and bwd(buf=odd) == 3 and bwd(dxt=9) == 4
     assert bwd(wsb=0) == 5
@@ -96,12 +98,14 @@ def test_argument_validation_happens_before_any_launch(L):
     p = L.falqon_proxy_update
 
     def upd(**kw):
-        a = dict(buf=ok, wq=ok, n=64, m=64, r=16, k=4, idx=ok, ws=ok, wsb=ws_bytes)
+        a = dict(buf=ok, wq=ok, n=64, m=64, r=16, k=4, idx=ok, sc=None, ws=ok, wsb=ws_bytes)
         a.update(kw)
-        return p(_vp(a["buf"]), _vp(a["wq"]), a["n"], a["m"], a["r"], a["k"], _vp(a["idx"]), 1, _vp(a["ws"]),
-                 a["wsb"], None)
+        return p(_vp(a["buf"]), _vp(a["wq"]), a["n"], a["m"], a["r"], a["k"], _vp(a["idx"]), 1, _vp(a["sc"]),
+                 _vp(a["ws"]), a["wsb"], None)
 
-    assert upd(buf=None) == 1 and upd(idx=None) == 1
+    assert upd(buf=None) == 1 and upd(idx=None) == 1 and upd(sc=odd) == 3
+    assert L.falqon_row_score_bytes(4096) == 8 * (4096 + 64) and L.falqon_row_score_bytes(100) == 8 * 102
+    assert L.falqon_row_score_bytes(0) == 0 and L.falqon_row_score_bytes(70000) == 0
     assert upd(k=0) == 2 and upd(k=65) == 2 and upd(m=131072, k=1) == 2
     assert upd(wq=odd) == 3
     assert upd(ws=None) == 5 and upd(wsb=16) == 5
