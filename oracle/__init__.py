@@ -55,6 +55,8 @@ def lib():
         L.orc_topk_rows.argtypes = [p, c.c_int64, c.c_int64, p]
         L.orc_proxy_update.argtypes = [p, p, c.c_int64, c.c_int64, c.c_int64, c.c_int64, p, c.c_int]
         L.orc_init_residual.argtypes = [p, p, c.c_float, c.c_int64, p]
+        L.orc_adapter_inner_grad.argtypes = [p, c.c_float, p, c.c_float, c.c_int64, c.c_int64, c.c_int64, p]
+        L.orc_da.argtypes = [p, c.c_float, p, c.c_int64, c.c_int64, c.c_int64, p, c.c_int64, p]
         L.orc_num_threads.restype = c.c_int
         _lib = L
     return _lib
@@ -235,6 +237,40 @@ def init_residual(w, wq, s_w) -> np.ndarray:
     e = np.empty(wf.shape, np.float32)
     lib().orc_init_residual(_ptr(wf), _ptr(q), float(s_w), wf.size, _ptr(e))
     return e
+
+
+def adapter_inner_grad(dyq, s_dy, btq, s_b) -> np.ndarray:
+    """G = bf16( dy~ . B~ / (s_dy s_b) ): the gradient at the adapter's inner activation A x (LoRA backward
+    equation, first product of dL/dA = B^T dL/dO x^T).  btq is B^T as E4M3 codes [r, m]; returns fp32 [T, r]."""
+    dyq = _c(dyq, np.uint8)
+    btq = _c(btq, np.uint8)
+    T, m = dyq.shape
+    r = btq.shape[0]
+    assert btq.shape == (r, m)
+    g = np.empty((T, r), np.float32)
+    lib().orc_adapter_inner_grad(_ptr(dyq), float(s_dy), _ptr(btq), float(s_b), T, m, r, _ptr(g))
+    return g
+
+
+def da(xq, s_x, g, rows=None) -> np.ndarray:
+    """(dL/dA)^T = x~^T . G / s_x, fp64 [rows of n, r] (LoRA backward equation, second product)."""
+    xq = _c(xq, np.uint8)
+    gg = _c(g, np.float32)
+    T, n = xq.shape
+    r = gg.shape[1]
+    assert gg.shape[0] == T
+    rs, nr = _sel(rows)
+    out = np.empty((nr if rs is not None else n, r), np.float64)
+    lib().orc_da(_ptr(xq), float(s_x), _ptr(gg), T, n, r, _ptr(rs), nr, _ptr(out))
+    return out
+
+
+def svd_factors(e, r: int):
+    """Both factors of the rank-r truncated SVD of E by the library's full SVD in fp64 (initialization
+    algorithm, line 5): B = U_r sqrt(S_r) [m, r], A = sqrt(S_r) V_r^T [r, n], and all singular values."""
+    u, sv, vt = np.linalg.svd(np.asarray(e, np.float64), full_matrices=False)
+    root = np.sqrt(sv[:r])
+    return u[:, :r] * root[None, :], root[:, None] * vt[:r], sv
 
 
 def svd_right_factor(e, r: int):

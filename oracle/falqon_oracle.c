@@ -442,6 +442,56 @@ void orc_init_residual(const float* w, const uint8_t* wq, float s_w, int64_t cou
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* Variant in which the adapter factor A is trained too (appendix "Ablation   */
+/* on matrix A update").  LoRA backward equation:                             */
+/*   dL/dA = B^T dL/dO x^T                                                    */
+/* In the layer's orientation (tokens first) that is two products:            */
+/*   G[t,p]     = sum_i dY[t,i] B[i,p]          (the gradient at A x)         */
+/*   dA^T[j,p]  = sum_t x[t,j] G[t,p]                                         */
+/* with the FP8 operands the layer already has: dy~ (E5M2, scale s_dy),       */
+/* x~ (E4M3, scale s_x), and B^T cast to E4M3 with a scale s_b of its own,    */
+/* stored as bt[p][i].  G is kept at 16-bit precision, like the saved O_A     */
+/* (the paper does not fix the precision of these small products):            */
+/*   G[t,p]    = bf16( ( sum_i dec5(dyq[t,i]) dec4(btq[p,i]) ) / (s_dy s_b) ) */
+/*   dAt[j,p]  = ( sum_t dec4(xq[t,j]) G[t,p] ) / s_x                         */
+/* ------------------------------------------------------------------------- */
+void orc_adapter_inner_grad(const uint8_t* dyq, float s_dy, const uint8_t* btq, float s_b,
+                            int64_t T, int64_t m, int64_t r, float* g_out)
+{
+    double lut5[256], lut4[256];
+    for (int c = 0; c < 256; ++c) { lut5[c] = orc_fp8_decode((uint8_t)c, 1); lut4[c] = orc_fp8_decode((uint8_t)c, 0); }
+    const double denom = (double)s_dy * (double)s_b;
+    #pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t p = 0; p < r; ++p) {
+            double acc = 0.0;
+            for (int64_t i = 0; i < m; ++i) acc += lut5[dyq[t * m + i]] * lut4[btq[p * m + i]];
+            g_out[t * r + p] = orc_round_bf16(acc / denom);
+        }
+    }
+}
+
+void orc_da(const uint8_t* xq, float s_x, const float* g, int64_t T, int64_t n, int64_t r,
+            const int64_t* row_sel, int64_t n_rows, double* out)
+{
+    double lut4[256];
+    for (int c = 0; c < 256; ++c) lut4[c] = orc_fp8_decode((uint8_t)c, 0);
+    if (!row_sel) n_rows = n;
+    #pragma omp parallel for schedule(dynamic, 8)
+    for (int64_t a = 0; a < n_rows; ++a) {
+        int64_t j = row_sel ? row_sel[a] : a;
+        double* acc = out + a * r;
+        for (int64_t p = 0; p < r; ++p) acc[p] = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            double xv = lut4[xq[t * n + j]];
+            const float* grow = g + t * r;
+            for (int64_t p = 0; p < r; ++p) acc[p] += xv * (double)grow[p];
+        }
+        for (int64_t p = 0; p < r; ++p) acc[p] = acc[p] / (double)s_x;
+    }
+}
+
 int orc_num_threads(void)
 {
     int nthreads = 1;
