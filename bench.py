@@ -505,6 +505,16 @@ def main():
     db_tmp = torch.empty(m, r, device="cuda")
     ms_db_wide = _events(lambda: fq.db_bf16(layer.dyq, layer.s_dy, layer.o_a, db_tmp, None, 0.0, layer.ws), it)
     del db_tmp
+    # variant that also forms the gradient of the adapter factor A (the paper's "+ Update matrix A" ablation row):
+    # two more products per layer step, on a random B^ cast to E4M3
+    bt = torch.randn(r, m, device="cuda", generator=torch.Generator(device="cuda").manual_seed(5)) * 0.05
+    btq = torch.empty(r, m, dtype=torch.uint8, device="cuda"); s_b = torch.zeros(1, device="cuda")
+    fq.quantize(bt, fq.E4M3, btq, s_b, layer.ws)
+    g_tmp = torch.empty(T, r, dtype=torch.bfloat16, device="cuda"); amax_g = torch.zeros(1, device="cuda")
+    dat_tmp = torch.empty(n, r, device="cuda")
+    ws_da = torch.empty(fq.workspace_bytes(T, m, n, r), dtype=torch.uint8, device="cuda")
+    ms_da = _median_events(lambda: fq.da(layer.dyq, layer.s_dy, btq, s_b, layer.xq, layer.s_x, g_tmp, amax_g, dat_tmp, ws_da), it)
+    del bt, btq, g_tmp, dat_tmp, ws_da
     layer.delta_buf.zero_()
     s_tmp = torch.zeros(1, device="cuda")
     ms_quant = _median_events(lambda: fq.quantize(x, fq.E4M3, layer.xq, s_tmp, layer.ws), it)
@@ -571,6 +581,11 @@ def main():
         "db_bf16_variant": {"ms": ms_db_wide, "flops": 2.0 * T * m * r,
                             "note": "dB = dy~^T O_A with O_A kept in bf16 (bf16 matrix cores), partial pass + ordered sum as "
                                     "two launches of their own; not in the timed step"},
+        "a_update_variant": {"da_ms": ms_da, "flops": 4.0 * T * m * r if n == m else 2.0 * T * r * (m + n),
+                             "step_with_da_ms": ms_per_step + ms_da, "slowdown": (ms_per_step + ms_da) / ms_per_step,
+                             "note": "falqon_da, the gradient of the adapter factor A (dL/dA = B^T dL/dO x^T) as two small "
+                                     "products; not in the timed step.  Paper, whole model on its GPU: 1.94 s against 1.80 s "
+                                     "per step (7B), 3.89 against 3.26 (13B) - context only"},
         "calls": {"melded_fwd_ms": ms_fwd, "melded_bwd_ms": ms_bwd, "proxy_update_ms": ms_upd},
     }
 

@@ -252,6 +252,33 @@ falqon_status falqon_db_bf16(const uint8_t* dyq, const float* s_dy, const void* 
                              void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Variant in which the adapter factor A is trained too (the paper's appendix "Ablation on matrix A
+ * update", which reports what forming this gradient costs): the gradient of A from the LoRA
+ * backward equation, dL/dA = B^T dL/dO x^T, as two products on the FP8 operands the melded calls
+ * leave behind:
+ *
+ *   g     = bf16( dyq . btq^T / (s_dy * s_b) )     [T, r]  gradient at the inner activation A x
+ *   d_at  = xq^T . g / s_x                          [n, r]  = (dL/dA)^T, fp32 accumulation
+ *
+ * g is kept at 16-bit precision like the saved O_A (the paper does not fix the precision of these
+ * small products); FP8 values are exact in bf16, so the second product runs on the bf16 matrix
+ * cores with nothing rounded before the accumulation.  B is implicit in the melded weight; a
+ * caller that wants this variant keeps B^T from the initialization (falqon_svd_right_factor's
+ * bt_out) cast to E4M3 with falqon_quantize.  Applying a change of A to the melded weight is not
+ * part of the method as published and not of this library.
+ *
+ *   dyq, s_dy  in   E5M2 [T, m] and scale, as falqon_melded_bwd returned them
+ *   btq, s_b   in   B^T as E4M3 codes [r, m] and its scale
+ *   xq, s_x    in   E4M3 [T, n] and scale, as falqon_melded_fwd returned them
+ *   g          out  bf16 [T, r];  amax_g  out  device scalar, max |g|
+ *   d_at       out  fp32 [n, r]
+ *   ws         at least falqon_workspace_bytes(T, m, n, r) bytes (n and m exchanged)
+ */
+falqon_status falqon_da(const uint8_t* dyq, const float* s_dy, const uint8_t* btq, const float* s_b,
+                        const uint8_t* xq, const float* s_x, int64_t T, int64_t n, int64_t m, int64_t r,
+                        void* g, float* amax_g, float* d_at, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Optimizer step into the proxy buffer: "DeltaBuffer <- Optimizer(dL/dB, lr)", the second line of
  * the loop of the paper's backward-and-update algorithm, with the optimizer its experiments name
  * (AdamW with a maximum gradient norm of 0.3; "Detailed experimental settings").  Two calls:
@@ -305,13 +332,16 @@ falqon_status falqon_adamw_delta(const float* d_b, float* exp_avg, float* exp_av
  * rows with squared norms sigma_out[i] (the Ritz values, approximations from below of the r
  * largest singular values, in descending order); the sign of each row is arbitrary.  The row space
  * converges to that of the exact truncated SVD at the rate (sigma_{l+1} / sigma_r)^(2 iters + 1).
+ * bt_out (nullable, fp32 [r, m]): the other factor, transposed, B^ = U_r sqrt(S_r) with the same
+ * signs, so that bt_out^T a_out approximates the rank-r part of E (only the A-update variant,
+ * falqon_da, needs it).
  * 16 <= r <= 120, r a multiple of 8; m, n multiples of 4; ws of falqon_svd_workspace_bytes(m, n, r).
  */
 falqon_status falqon_init_residual(const float* w, const uint8_t* wq, const float* s_w, int64_t m, int64_t n,
                                    float* e, void* stream);
 size_t falqon_svd_workspace_bytes(int64_t m, int64_t n, int64_t r);
 falqon_status falqon_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega,
-                                      int iters, float* a_out, float* sigma_out,
+                                      int iters, float* a_out, float* sigma_out, float* bt_out,
                                       void* ws, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus

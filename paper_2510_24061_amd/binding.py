@@ -73,7 +73,9 @@ def lib():
         L.falqon_svd_workspace_bytes.restype = c.c_size_t
         L.falqon_svd_workspace_bytes.argtypes = [i64, i64, i64]
         L.falqon_svd_right_factor.restype = c.c_int
-        L.falqon_svd_right_factor.argtypes = [f32p, i64, i64, i64, f32p, c.c_int, f32p, f32p, vp, c.c_size_t, vp]
+        L.falqon_svd_right_factor.argtypes = [f32p, i64, i64, i64, f32p, c.c_int, f32p, f32p, f32p, vp, c.c_size_t, vp]
+        L.falqon_da.restype = c.c_int
+        L.falqon_da.argtypes = [vp, f32p, vp, f32p, vp, f32p, i64, i64, i64, i64, vp, f32p, f32p, vp, c.c_size_t, vp]
         _lib = L
     return _lib
 
@@ -237,11 +239,24 @@ def svd_workspace_bytes(m: int, n: int, r: int) -> int:
     return int(lib().falqon_svd_workspace_bytes(m, n, r))
 
 
-def svd_right_factor(e, r: int, omega, iters: int, a_out, sigma_out, ws) -> None:
-    """a_out = sqrt(S_r) V_r^T of e (fp32 [m, n]); omega is a Gaussian fp32 [r + 8, n] start matrix."""
-    _dev(e, omega, a_out, sigma_out, ws)
+def da(dyq, s_dy, btq, s_b, xq, s_x, g, amax_g, d_at, ws) -> None:
+    """Gradient of the adapter factor A: g = bf16(dyq btq^T / (s_dy s_b)), d_at = xq^T g / s_x (fp32 [n, r]).
+    ws: workspace_bytes(T, m, n, r) bytes (n and m exchanged)."""
+    _dev(dyq, s_dy, btq, s_b, xq, s_x, g, amax_g, d_at, ws)
+    T, m = dyq.shape
+    n = xq.shape[1]
+    r = btq.shape[0]
+    st = lib().falqon_da(_p(dyq), _p(s_dy), _p(btq), _p(s_b), _p(xq), _p(s_x), T, n, m, r, _p(g), _p(amax_g), _p(d_at),
+                         _p(ws), ws.numel() * ws.element_size(), _stream())
+    _check(st, "falqon_da")
+
+
+def svd_right_factor(e, r: int, omega, iters: int, a_out, sigma_out, ws, bt_out=None) -> None:
+    """a_out = sqrt(S_r) V_r^T of e (fp32 [m, n]); omega is a Gaussian fp32 [r + 8, n] start matrix.
+    bt_out (fp32 [r, m], optional): the left factor transposed, (U_r sqrt(S_r))^T."""
+    _dev(e, omega, a_out, sigma_out, ws, bt_out)
     m, n = e.shape
-    st = lib().falqon_svd_right_factor(_p(e), m, n, r, _p(omega), iters, _p(a_out), _p(sigma_out), _p(ws),
+    st = lib().falqon_svd_right_factor(_p(e), m, n, r, _p(omega), iters, _p(a_out), _p(sigma_out), _p(bt_out), _p(ws),
                                        ws.numel() * ws.element_size(), _stream())
     _check(st, "falqon_svd_right_factor")
 

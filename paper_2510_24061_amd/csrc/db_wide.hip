@@ -5,7 +5,9 @@
 //
 // An E5M2 value has two mantissa bits and a five-bit exponent, so it is exactly representable in
 // bf16; the product therefore runs on the bf16 matrix cores with nothing rounded before the fp32
-// accumulation.  Same split into fp32 partials over token ranges and the same ordered second pass
+// accumulation.  The same kernel with E4M3 codes on the left (three mantissa bits: exact in bf16
+// too) forms the second product of the gradient of the adapter factor A (LoRA backward equation),
+//   dA^T[j,p] = ( sum_t value4(xq[t,j]) * g[t,p] ) / s_x.  Same split into fp32 partials over token ranges and the same ordered second pass
 // as the FP8 variant.
 //
 // Operands for a contraction over tokens (the strided dimension of both tensors):
@@ -30,11 +32,15 @@ constexpr size_t kWideLdsBytes = static_cast<size_t>(kWideTiles) * kWideTileByte
 
 __device__ __attribute__((aligned(16))) uint8_t g_wide_zero16[16];
 
-// two E5M2 codes (the selected 16-bit half of w) -> two bf16 in one dword, first code in the low half
+// two FP8 codes (the selected 16-bit half of w; E5M2 if LEFT_E5M2, else E4M3) -> two bf16 in one
+// dword, first code in the low half
+template <bool LEFT_E5M2>
 __device__ __forceinline__ int widen2(int w, bool upper_half)
 {
-    const v2f f = upper_half ? __builtin_amdgcn_cvt_pk_f32_bf8(w, true) : __builtin_amdgcn_cvt_pk_f32_bf8(w, false);
-    // the value has at most three significant bits: the upper half of the fp32 pattern is the bf16
+    v2f f;
+    if (LEFT_E5M2) f = upper_half ? __builtin_amdgcn_cvt_pk_f32_bf8(w, true) : __builtin_amdgcn_cvt_pk_f32_bf8(w, false);
+    else f = upper_half ? __builtin_amdgcn_cvt_pk_f32_fp8(w, true) : __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
+    // the value has at most four significant bits: the upper half of the fp32 pattern is the bf16
     return static_cast<int>(__builtin_amdgcn_perm(__float_as_uint(f[1]), __float_as_uint(f[0]), 0x07060302u));
 }
 
@@ -44,6 +50,7 @@ __device__ __forceinline__ int oat_offset(int p, int token)
     return p * (BT * 2) + ((((token >> 3) ^ (p & 15)) << 4) | ((token & 7) << 1));
 }
 
+template <bool LEFT_E5M2>
 __global__ void __launch_bounds__(kThreads)
 db_wide_partial_kernel(const DbArgs d)
 {
@@ -135,8 +142,8 @@ db_wide_partial_kernel(const DbArgs d)
                 const uint8_t* pa = s_dy + trow * BI + ((((feat >> 4) ^ swz_t<CH_DY>(trow)) << 4) | (feat & 15));
                 const v2i c8 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((v2i __attribute__((address_space(3)))*)(pa));
                 v4i aw;
-                aw[0] = widen2(c8[0], false); aw[1] = widen2(c8[0], true);
-                aw[2] = widen2(c8[1], false); aw[3] = widen2(c8[1], true);
+                aw[0] = widen2<LEFT_E5M2>(c8[0], false); aw[1] = widen2<LEFT_E5M2>(c8[0], true);
+                aw[2] = widen2<LEFT_E5M2>(c8[1], false); aw[3] = widen2<LEFT_E5M2>(c8[1], true);
                 const v8bf a = __builtin_bit_cast(v8bf, aw);
 #pragma unroll
                 for (int b = 0; b < 2; ++b) {
@@ -162,14 +169,20 @@ db_wide_partial_kernel(const DbArgs d)
 
 }  // namespace
 
-hipError_t launch_db_wide_partial(const DbArgs& d, hipStream_t stream)
+template <bool LEFT_E5M2>
+static hipError_t launch_wide(const DbArgs& d, hipStream_t stream)
 {
     const dim3 grid(static_cast<unsigned>(d.i_tiles), static_cast<unsigned>(d.splits), static_cast<unsigned>(d.p_tiles));
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&db_wide_partial_kernel),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&db_wide_partial_kernel<LEFT_E5M2>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(kWideLdsBytes));
     if (e != hipSuccess) return e;
-    db_wide_partial_kernel<<<grid, kThreads, kWideLdsBytes, stream>>>(d);
+    db_wide_partial_kernel<LEFT_E5M2><<<grid, kThreads, kWideLdsBytes, stream>>>(d);
     return hipGetLastError();
+}
+
+hipError_t launch_db_wide_partial(const DbArgs& d, hipStream_t stream, bool left_e5m2)
+{
+    return left_e5m2 ? launch_wide<true>(d, stream) : launch_wide<false>(d, stream);
 }
 
 }  // namespace falqon

@@ -272,6 +272,50 @@ falqon_status falqon_db_bf16(const uint8_t* dyq, const float* s_dy, const void* 
     return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }
 
+falqon_status falqon_da(const uint8_t* dyq, const float* s_dy, const uint8_t* btq, const float* s_b,
+                        const uint8_t* xq, const float* s_x, int64_t T, int64_t n, int64_t m, int64_t r,
+                        void* g, float* amax_g, float* d_at, void* ws, size_t ws_bytes, void* stream)
+{
+    if (bad_layer_shape(T, n, m, r)) return FALQON_ERR_SHAPE;
+    if (!dyq || !s_dy || !btq || !s_b || !xq || !s_x || !g || !amax_g || !d_at) return FALQON_ERR_NULL;
+    if (misaligned(dyq) || misaligned(btq) || misaligned(xq) || misaligned(g) || misaligned(d_at) ||
+        (reinterpret_cast<uintptr_t>(s_dy) & 3u) || (reinterpret_cast<uintptr_t>(s_b) & 3u) ||
+        (reinterpret_cast<uintptr_t>(s_x) & 3u) || (reinterpret_cast<uintptr_t>(amax_g) & 3u))
+        return FALQON_ERR_ALIGN;
+    // the second product has the layer's input width in the place of its output width
+    const WsLayout L = ws_layout(T, m, n, r);
+    if (!ws || ws_bytes < L.total) return FALQON_ERR_WORKSPACE;
+    if (misaligned(ws)) return FALQON_ERR_ALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t* w8 = static_cast<uint8_t*>(ws);
+
+    // G <- dy~ B~ / (s_dy s_b): a product with only r output columns, so K is split over workgroups;
+    // fp32 partials, then the pass that adds them in order, rounds to bf16 and takes the maximum
+    hipError_t e = launch_zero_word(reinterpret_cast<uint32_t*>(amax_g), st);
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+    const int splits = oa_splits(T, r);
+    int64_t kps = (m + splits - 1) / splits;
+    kps = (kps + 127) / 128 * 128;
+    float* part = reinterpret_cast<float*>(w8 + L.oa_partials);
+    GemmArgs h;
+    h.a = dyq; h.lda = m; h.a_fmt = 1;
+    h.b = btq; h.ldb = m; h.b_is_kn = 0;
+    h.M = T; h.N = r; h.K = m;
+    h.sa = s_dy; h.sb = s_b;
+    h.c0 = part; h.ldc0 = r; h.c0_is_f32 = 1; h.n_split = r;
+    h.c1 = nullptr; h.ldc1 = 0; h.amax1 = nullptr;
+    h.splits = splits; h.k_per_split = kps;
+    e = launch_gemm(h, st);
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+    e = launch_sum_partials_bf16(part, splits, T * r, static_cast<uint16_t*>(g), reinterpret_cast<uint32_t*>(amax_g), st);
+    if (e != hipSuccess) return FALQON_ERR_HIP;
+    // dA^T <- x~^T G / s_x on the bf16 matrix cores (E4M3 is exact in bf16), token splits, ordered sum
+    const DbArgs d = make_db_args(xq, g, nullptr, T, n, r, reinterpret_cast<float*>(w8 + L.db_partials), db_splits(T, n));
+    e = launch_db_wide_partial(d, st, false);
+    if (e == hipSuccess) e = launch_db_reduce(d, s_x, d_at, nullptr, 0.0f, st);
+    return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
+}
+
 falqon_status falqon_proxy_update(float* delta_buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, int64_t k,
                                   int32_t* idx_out, int clear_selected, const double* row_scores,
                                   void* ws, size_t ws_bytes, void* stream)
@@ -418,16 +462,17 @@ size_t falqon_svd_workspace_bytes(int64_t m, int64_t n, int64_t r)
 }
 
 falqon_status falqon_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega,
-                                      int iters, float* a_out, float* sigma_out,
+                                      int iters, float* a_out, float* sigma_out, float* bt_out,
                                       void* ws, size_t ws_bytes, void* stream)
 {
     if (bad_svd_shape(m, n, r) || iters < 0 || iters > 64) return FALQON_ERR_SHAPE;
     if (!e || !omega || !a_out || !sigma_out) return FALQON_ERR_NULL;
-    if (misaligned(e) || misaligned(omega) || misaligned(a_out) || (reinterpret_cast<uintptr_t>(sigma_out) & 3u))
+    if (misaligned(e) || misaligned(omega) || misaligned(a_out) || (reinterpret_cast<uintptr_t>(sigma_out) & 3u) ||
+        (bt_out && misaligned(bt_out)))
         return FALQON_ERR_ALIGN;
     if (!ws || ws_bytes < svd_layout(m, n, r).total) return FALQON_ERR_WORKSPACE;
     if (misaligned(ws)) return FALQON_ERR_ALIGN;
-    hipError_t err = launch_svd_right_factor(e, m, n, r, omega, iters, a_out, sigma_out, static_cast<uint8_t*>(ws),
+    hipError_t err = launch_svd_right_factor(e, m, n, r, omega, iters, a_out, sigma_out, bt_out, static_cast<uint8_t*>(ws),
                                              static_cast<hipStream_t>(stream));
     return err == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
 }

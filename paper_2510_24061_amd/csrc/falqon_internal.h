@@ -100,7 +100,8 @@ hipError_t launch_db_partial(const DbArgs& d, hipStream_t stream);
 hipError_t launch_db_reduce(const DbArgs& d, const float* s_dy, float* d_b, float* delta_buf, float lr,
                             hipStream_t stream, double* score = nullptr);
 // Variant with O_A kept in bf16 (db_wide.hip): d.amax_oa is not read and may be null, also in the reduce.
-hipError_t launch_db_wide_partial(const DbArgs& d, hipStream_t stream);
+// left_e5m2 = false: the codes in d.dyq are E4M3 (the second product of the gradient of A, with x~ on the left).
+hipError_t launch_db_wide_partial(const DbArgs& d, hipStream_t stream, bool left_e5m2 = true);
 // Input-gradient GEMM g ([K,N] right operand, E5M2 left operand, 256x256 tiles) and the partial pass
 // of the adapter gradient in one launch: both read only dy~ (and O_A, the weight).
 bool gemm_dx_db_pair_supported(const GemmArgs& g);
@@ -125,8 +126,9 @@ hipError_t launch_init_residual(const float* w, const uint8_t* wq, const float* 
                                 hipStream_t stream);
 struct SvdLayout { size_t z, y, h, p, lambda, order, total; };   // offsets into the workspace, l = r + 8 vectors
 SvdLayout svd_layout(int64_t m, int64_t n, int64_t r);
+// bt_out (nullable): the left factor, transposed: B^ = U_r sqrt(S_r) as fp32 [r, m]
 hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega, int iters,
-                                   float* a_out, float* sigma_out, uint8_t* ws, hipStream_t stream);
+                                   float* a_out, float* sigma_out, float* bt_out, uint8_t* ws, hipStream_t stream);
 
 // ---- optimizer step into the proxy buffer (optimizer.hip) ------------------------------------
 // partials: at least 256 doubles of scratch

@@ -302,19 +302,22 @@ jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p
 __global__ void __launch_bounds__(kThreads)
 rotate_kernel(const float* __restrict__ z, int l, int64_t n, const double* __restrict__ p,
               const double* __restrict__ lambda, const int* __restrict__ order, int r,
-              float* __restrict__ a_out, float* __restrict__ sigma_out)
+              float* __restrict__ a_out, float* __restrict__ sigma_out, int inverse_scale)
 {
     const int k = blockIdx.y;
     const int col = order[k];
     const double lam = lambda[col] > 0.0 ? lambda[col] : 0.0;
-    const double scale = sqrt(sqrt(lam));
+    // right factor: z holds unit vectors, row k becomes sqrt(sigma_k) v_k.  Left factor (inverse_scale):
+    // z holds E v (length sigma_k u_k after the rotation), row k becomes sqrt(sigma_k) u_k.
+    const double root = sqrt(sqrt(lam));
+    const double scale = inverse_scale ? (root > 0.0 ? 1.0 / root : 0.0) : root;
     const int64_t j = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
     if (j < n) {
         double acc = 0.0;
         for (int c = 0; c < l; ++c) acc += p[c * l + col] * static_cast<double>(z[static_cast<int64_t>(c) * n + j]);
         a_out[static_cast<int64_t>(k) * n + j] = static_cast<float>(scale * acc);
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) sigma_out[k] = static_cast<float>(sqrt(lam));
+    if (blockIdx.x == 0 && threadIdx.x == 0 && sigma_out) sigma_out[k] = static_cast<float>(sqrt(lam));
 }
 
 }  // namespace
@@ -363,7 +366,7 @@ static hipError_t orthonormalize_rows(float* v, int l, int64_t len, double* h, d
 }
 
 hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega, int iters,
-                                   float* a_out, float* sigma_out, uint8_t* ws, hipStream_t stream)
+                                   float* a_out, float* sigma_out, float* bt_out, uint8_t* ws, hipStream_t stream)
 {
     const int l = static_cast<int>(r) + 8;
     const SvdLayout L = svd_layout(m, n, r);
@@ -402,8 +405,14 @@ hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t
     jacobi_eig_kernel<<<1, kThreads, lds, stream>>>(h, l, p, lambda, order, 14);
     FQ_CHECK_LAUNCH();
     rotate_kernel<<<dim3(static_cast<unsigned>((n + kThreads - 1) / kThreads), static_cast<unsigned>(r)), kThreads, 0,
-                    stream>>>(z, l, n, p, lambda, order, static_cast<int>(r), a_out, sigma_out);
+                    stream>>>(z, l, n, p, lambda, order, static_cast<int>(r), a_out, sigma_out, 0);
     FQ_CHECK_LAUNCH();
+    if (bt_out) {
+        // y still holds E z^T: its rotation by the same eigenvectors is sigma_k u_k, the left singular vectors
+        rotate_kernel<<<dim3(static_cast<unsigned>((m + kThreads - 1) / kThreads), static_cast<unsigned>(r)), kThreads, 0,
+                        stream>>>(y, l, m, p, lambda, order, static_cast<int>(r), bt_out, nullptr, 1);
+        FQ_CHECK_LAUNCH();
+    }
 #undef FQ_CHECK_LAUNCH
     return hipSuccess;
 }

@@ -152,6 +152,8 @@ class MeldedLoRALinear(torch.nn.Module):
         self.idx = torch.zeros(top_k, dtype=torch.int32, device=dev)
         self.exp_avg = None
         self.exp_avg_sq = None
+        self.btq = None                 # B^T as E4M3 codes [r, m] and its scale: only for the A-update variant
+        self.s_b = None
         self._ws = None
         # keeps autograd's backward running when the input carries no gradient; never receives one itself
         self._anchor = torch.nn.Parameter(torch.zeros(1, dtype=torch.float32, device=dev))
@@ -176,10 +178,12 @@ class MeldedLoRALinear(torch.nn.Module):
         self.delta_buf.zero_()
 
     @torch.no_grad()
-    def init_from_weight(self, w: torch.Tensor, iters: int = 6, seed: int = 0) -> torch.Tensor:
+    def init_from_weight(self, w: torch.Tensor, iters: int = 6, seed: int = 0, keep_left_factor: bool = False) -> torch.Tensor:
         """The whole initialization algorithm on the GPU: W~, s_w <- Q(W); E = DQ(W~) - W;
         A^ <- right factor of the rank-r SVD of E; A~ <- cast(A^ * s_w); buffer <- 0.
-        Returns the Ritz values (approximate leading singular values of E)."""
+        Returns the Ritz values (approximate leading singular values of E).
+        keep_left_factor: also keep B^ (transposed, cast to E4M3 with a scale of its own) in `btq`, `s_b`;
+        only the variant that forms the gradient of A (binding.da) reads it."""
         dev = self.wq.device
         m, n, r = self.out_features, self.in_features, self.rank
         w32 = w.to(device=dev, dtype=torch.float32).contiguous()
@@ -191,9 +195,14 @@ class MeldedLoRALinear(torch.nn.Module):
         a_hat = torch.empty(r, n, dtype=torch.float32, device=dev)
         sigma = torch.empty(r, dtype=torch.float32, device=dev)
         svd_ws = torch.empty(_b.svd_workspace_bytes(m, n, r), dtype=torch.uint8, device=dev)
-        _b.svd_right_factor(e, r, omega, iters, a_hat, sigma, svd_ws)
+        bt = torch.empty(r, m, dtype=torch.float32, device=dev) if keep_left_factor else None
+        _b.svd_right_factor(e, r, omega, iters, a_hat, sigma, svd_ws, bt_out=bt)
         s_tmp = torch.zeros(1, dtype=torch.float32, device=dev)
         _b.quantize(a_hat, _b.E4M3, self.wq[m:], s_tmp, ws, scale_in=self.s_w)
+        if keep_left_factor:
+            self.btq = torch.empty(r, m, dtype=torch.uint8, device=dev)
+            self.s_b = torch.zeros(1, dtype=torch.float32, device=dev)
+            _b.quantize(bt, _b.E4M3, self.btq, self.s_b, ws)
         self.delta_buf.zero_()
         return sigma
 

@@ -156,12 +156,12 @@ def test_initialization_argument_validation(L):
     svd = L.falqon_svd_right_factor
     wsb = L.falqon_svd_workspace_bytes(256, 256, 16)
 
-    def f(e=ok, m=256, n=256, r=16, om=ok, it=2, a=ok, sg=ok, ws=ok, wb=wsb):
-        return svd(_vp(e), m, n, r, _vp(om), it, _vp(a), _vp(sg), _vp(ws), wb, None)
+    def f(e=ok, m=256, n=256, r=16, om=ok, it=2, a=ok, sg=ok, bt=None, ws=ok, wb=wsb):
+        return svd(_vp(e), m, n, r, _vp(om), it, _vp(a), _vp(sg), _vp(bt), _vp(ws), wb, None)
 
     assert f(e=None) == 1 and f(om=None) == 1 and f(a=None) == 1 and f(sg=None) == 1
     assert f(r=12) == 2 and f(r=128) == 2 and f(m=254) == 2 and f(it=-1) == 2 and f(it=100) == 2
-    assert f(a=odd) == 3 and f(ws=None) == 5 and f(wb=wsb - 1) == 5
+    assert f(a=odd) == 3 and f(bt=odd) == 3 and f(ws=None) == 5 and f(wb=wsb - 1) == 5
 
 
 def test_db_bf16_argument_validation(L):
@@ -214,3 +214,17 @@ def test_fp8_gemm_argument_validation(L):
     assert g(side=odd, r=64, ws=ok, wsb=big) == 3
     assert g(side=ok, r=64, ws=ok, wsb=big, kn=1, af=0) == 4            # input-gradient orientation takes E5M2
     assert g(side=ok, r=64, ws=ok, wsb=big, kn=0, af=1) == 4
+
+
+def test_da_argument_validation(L):
+    f = L.falqon_da
+    ok, odd = _vp(0x10000), _vp(0x10004)
+    big = L.falqon_workspace_bytes(64, 128, 64, 16)              # (T, m, n, r): n and m exchanged
+
+    def g(dyq=ok, btq=ok, xq=ok, T=64, n=64, m=128, r=16, gg=ok, am=ok, dat=ok, ws=ok, wb=big):
+        return f(dyq, ok, btq, ok, xq, ok, T, n, m, r, gg, am, dat, ws, wb, None)
+
+    assert g(dyq=None) == 1 and g(btq=None) == 1 and g(xq=None) == 1 and g(gg=None) == 1 and g(dat=None) == 1
+    assert g(r=8) == 2 and g(n=72) == 2 and g(T=0) == 2
+    assert g(xq=odd) == 3 and g(dat=odd) == 3
+    assert g(ws=None) == 5 and g(wb=big - 1) == 5
