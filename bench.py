@@ -38,7 +38,7 @@ WARMUP_FLOOR_S = 0.3
 # rocprofv3 --pmc FETCH_SIZE (scaled by the plain-copy calibration) + WRITE_SIZE runs of this command;
 # the figures and the commands are in the committed summary named below.
 TRAFFIC_SOURCE = "profiles/bench_config2_pmc_hbm_traffic_and_mfma.md"
-TRAFFIC_BYTES = {"gemm_fwd_tail_kernel": None, "gemm_dx_tail_kernel": None}
+TRAFFIC_BYTES = {"gemm_fwd_tail_kernel": 158.1e6, "gemm_dx_tail_kernel": 157.6e6}
 
 
 def _events(fn, iters):
@@ -620,6 +620,9 @@ def main():
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, d, min(args.cpu_sample_tokens, T), args.cpu_reps)
+        if args.config == 2:
+            c1 = workloads.CONFIGS[1]
+            out["cpu_baseline_config1"] = cpu_baseline(c1, workloads.config_layer_inputs(1), c1.T, 20)
     if not args.no_context and args.config == 2:
         # the two MLP projections of the same model (config 3), time-capped
         sub_steps = max(20, min(200, args.steps))
