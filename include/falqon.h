@@ -213,16 +213,20 @@ falqon_status falqon_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t 
  * K and N must be multiples of 16.
  *
  * With side != NULL it is the product launch of a melded call, exactly as that call issues it
- * (one launch; what the call adds is the quantizer before it and the ordered sum after it): the
- * workgroups of the product also form the adapter's small product as fp32 partials in side_ws.
+ * (one launch; what the call adds is the quantizer before it and, where the adapter's product
+ * leaves the launch as partial sums, the ordered sum after it): the workgroups of the product
+ * also form the adapter's small product, into side_ws.
  *   b_is_kn = 0 (melded forward; a = x~ E4M3 [T, n], b = backbone rows [m, n]):
- *       side = adapter rows A~ [r, n] E4M3; partials of x~ A~^T over slices of K
+ *       side = adapter rows A~ [r, n] E4M3; x~ A~^T, finished (bf16) where every tile row has
+ *       enough tile columns to share it out (4 ceil(m / 256) >= r), else fp32 partials over
+ *       slices of K
  *   b_is_kn = 1 (melded backward; a = dy~ E5M2 [T, m], b = backbone rows [m, n]):
  *       side = O_A cast to E4M3 [T, r]; partials of dy~^T O_A~ over groups of tokens
  *   side_ws  scratch of at least falqon_workspace_bytes(T, n, m, r) bytes
- * Only for shapes at which the melded calls use this launch (large products, r <= 64, the adapter
- * columns not inside the backbone's last tile column); FALQON_ERR_SHAPE otherwise.  The partials'
- * layout is internal; the entry exists so that this launch can be timed on its own.
+ * Only for shapes at which the melded calls use this launch (large products, the adapter columns
+ * not inside the backbone's last tile column, r <= 64 unless the forward product is finished in
+ * the launch); FALQON_ERR_SHAPE otherwise.  What side_ws holds afterwards is internal; the entry
+ * exists so that this launch can be timed on its own.
  */
 falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t* b, int b_is_kn,
                               int64_t M, int64_t N, int64_t K, const float* s_a, const float* s_b,

@@ -151,9 +151,10 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
         e = launch_gemm(g, st);
         return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
     }
-    // O_A <- x~ A~^T / (s_w s_x) as fp32 partials over K slices, then one pass that adds them in
-    // order, rounds to bf16 and takes the maximum.  On the large tiles every backbone workgroup
-    // forms a share of the partials as a side job after its own tile.
+    // O_A <- x~ A~^T / (s_w s_x).  On the large tiles the backbone workgroups form it: inside their
+    // own K-steps, finished, where a tile row has enough tile columns to share it out; else as a
+    // side job ahead of the tile that leaves fp32 partials over K slices, which one more pass adds
+    // in order, rounds to bf16 and takes the maximum of.
     float* part = reinterpret_cast<float*>(w8 + L.oa_partials);
     const OaTailPlan po = plan_oa_tail(T, n, m, r);
     if (po.use) {
@@ -162,8 +163,9 @@ falqon_status falqon_melded_fwd(const void* x, const uint8_t* wq, const float* s
         t.row_parts = po.row_parts;
         e = launch_gemm_fwd_tail(g, t, st);
         if (e != hipSuccess) return FALQON_ERR_HIP;
-        e = launch_sum_partials_bf16(part, po.splits, T * r, static_cast<uint16_t*>(o_a),
-                                     reinterpret_cast<uint32_t*>(amax_oa), st);
+        if (po.splits > 0)                                       // (no partials: the launch wrote O_A and its maximum)
+            e = launch_sum_partials_bf16(part, po.splits, T * r, static_cast<uint16_t*>(o_a),
+                                         reinterpret_cast<uint32_t*>(amax_oa), st);
         return e == hipSuccess ? FALQON_OK : FALQON_ERR_HIP;
     }
     // Otherwise: the same GEMM kernel on the adapter rows, K split over workgroups.  Nothing orders
@@ -391,6 +393,9 @@ falqon_status falqon_fp8_gemm(const uint8_t* a, falqon_fmt a_fmt, const uint8_t*
         if (!po.use || (m + r + tile - 1) / tile == (m + tile - 1) / tile) return FALQON_ERR_SHAPE;
         t.partial = reinterpret_cast<float*>(w8 + L.oa_partials); t.splits = po.splits; t.steps_per_split = po.steps_per_split;
         t.row_parts = po.row_parts;
+        if (po.splits == 0) {                                    // O_A (bf16) instead of partials
+            g.c1 = w8 + L.oa_partials; g.ldc1 = r;
+        }
         e = launch_gemm_fwd_tail(g, t, st);
     } else {
         const DbTailPlan pd = plan_db_tail(M, n, m, r);

@@ -61,10 +61,13 @@ int64_t gemm_tile_n(int64_t M, int64_t N);   // width of the output tiles launch
 bool gemm_fwd_pair_supported(const GemmArgs& g, const GemmArgs& h);
 hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_t stream);
 
-// Side job that every 256x256 backbone tile performs after its own tile (gemm.hip).
-//   forward launch:        side = adapter rows A~ [r][K] (row stride g.ldb); partial[splits][M][r], rescaled;
-//                          tile columns in sets of row_parts: set s < splits covers K-steps
-//                          [s * steps_per_split, +steps_per_split), each member a part of the token rows
+// What every 256x256 backbone tile does for the adapter besides its own tile (gemm.hip).
+//   forward launch:        side = adapter rows A~ [r][K] (row stride g.ldb).
+//                          splits > 0: partial[splits][M][r], rescaled; tile columns in sets of
+//                          row_parts: set s < splits covers K-steps [s * steps_per_split,
+//                          +steps_per_split), each member a part of the token rows.
+//                          splits = 0 (row_parts = 0): no partials; the launch writes O_A as bf16 to
+//                          g.c1 (row stride g.ldc1) and raises g.amax1 (if not null) to its maximum
 //   input-gradient launch: side = O_A codes [T][r] (E4M3, cast by the dy quantizer's cast pass);
 //                          partial[groups][m][r], raw sums; splits / steps_per_split unused
 struct TailArgs {

@@ -36,6 +36,7 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v2i __attribute__((ext_vector_type(2)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 
 #define FQ_GLOBAL_PTR(p) ((const void __attribute__((address_space(1)))*)(p))
 #define FQ_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
@@ -332,16 +333,17 @@ constexpr int gemm_lds_bytes() { return (3 * WM * MB + 2 * WN * NB) * 32 * BK; }
 
 // One output tile.  `bid` is the workgroup's index in a grid of 8 * chunk workgroups whose index
 // modulo 8 is the XCD it runs on, `split` its K split; `lds` is gemm_lds_bytes() of LDS, 1 KB aligned.
-// TAIL selects a side job that the workgroup performs ahead of its tile (see the side-job functions
-// above): 0 none, 1 a K slice of the adapter product O_A (forward), 2 a slice of the adapter
-// gradient dB (input-gradient launch).
+// TAIL selects what the workgroup does for the adapter besides its tile: 0 nothing; 1 a K slice of
+// the adapter product O_A as a side job ahead of the tile (forward); 2 a slice of the adapter
+// gradient dB as a side job ahead of the tile (input-gradient launch); 3 blocks of O_A formed inside
+// the tile's own K-steps, finished and written as bf16 with their maximum (forward).
 template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT, int TAIL = 0>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, const int tiles_n, const int chunk,
                                           const int bid, const int split, uint8_t* const lds,
                                           const TailArgs* const tail = nullptr)
 {
     static_assert(TAIL == 0 || (WM == 2 && WN == 2 && MB == 4 && NB == 4), "side jobs ride on the 256x256 tile only");
-    static_assert(TAIL != 1 || (!B_KN && A_FMT == 0), "the O_A slice belongs to the forward product");
+    static_assert((TAIL != 1 && TAIL != 3) || (!B_KN && A_FMT == 0), "the adapter product belongs to the forward product");
     static_assert(TAIL != 2 || (B_KN && A_FMT == 1), "the dB slice belongs to the input-gradient product");
     constexpr int BM = WM * MB * 32, BN = WN * NB * 32, NW = WM * WN;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
@@ -550,6 +552,54 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
         else if (f < N_FRAG) af[kh][f - NB] = read_a(sA, f - NB, kh);
     };
 
+    // ---- adapter product riding on the tile's own K-steps (TAIL == 3) ----------------------------
+    // O_A of a tile row is 16 blocks of 16 token rows by r / 16 blocks of 16 ranks.  Wave w of tile
+    // column c takes block u = 4 c + w: token rows [16 (u % 16), +16) of the tile row, ranks
+    // [16 (u / 16), +16), over all of K.  Its token operand is read from the left tile that sits in
+    // LDS for the tile's own product, its adapter operand straight from memory one step ahead; one
+    // 16x16x128 MFMA per K-step and no partial results.  Waves without a block run the same
+    // instructions on clamped rows and store nothing, so the loop carries no branch for it.
+    v4f accx = {0.0f, 0.0f, 0.0f, 0.0f};
+    float ride_max = 0.0f;
+    v8i sb;
+    const int ride_u = tile_n * NW + wave;
+    const int ride_row = (ride_u & 15) * 16 + (lane & 15);     // row of the left tile
+    const int ride_rank0 = (ride_u >> 4) * 16;
+    // adapter operand of stage s; `inside`: the stage lies fully inside K (otherwise chunks beyond K are zeros)
+    const uint8_t* ride_src = nullptr;
+    if constexpr (TAIL == 3) {
+        const int r = static_cast<int>(tail->r);
+        const int row = ride_rank0 + (lane & 15);
+        ride_src = tail->side + static_cast<int64_t>(row < r ? row : r - 1) * g.ldb + (lane >> 4) * 32;
+    }
+    auto ride_load = [&](int s, bool inside) {
+        const uint8_t* p = ride_src + static_cast<int64_t>(s) * BK;
+        const int64_t gk = static_cast<int64_t>(s) * BK + (lane >> 4) * 32;
+        const v4i lo = *reinterpret_cast<const v4i*>(inside || gk < g.K ? p : g_zero16);
+        const v4i hi = *reinterpret_cast<const v4i*>(inside || gk + 16 < g.K ? p + 16 : g_zero16);
+        sb[0] = lo[0]; sb[1] = lo[1]; sb[2] = lo[2]; sb[3] = lo[3];
+        sb[4] = hi[0]; sb[5] = hi[1]; sb[6] = hi[2]; sb[7] = hi[3];
+    };
+    auto ride_read = [&](const uint8_t* tile) -> v8i {         // lane l: row l % 16, K bytes [32 (l / 16), +32)
+        const int cb = (lane >> 4) * 2;
+        const int sw = swz_kc(ride_row);
+        const uint8_t* base = tile + ride_row * BK;
+        const v4i lo = *reinterpret_cast<const v4i*>(base + ((cb ^ sw) << 4));
+        const v4i hi = *reinterpret_cast<const v4i*>(base + (((cb + 1) ^ sw) << 4));
+        v8i x;
+        x[0] = lo[0]; x[1] = lo[1]; x[2] = lo[2]; x[3] = lo[3];
+        x[4] = hi[0]; x[5] = hi[1]; x[6] = hi[2]; x[7] = hi[3];
+        return x;
+    };
+    v8i xa;
+    // Written as assembly with the accumulator in ordinary vector registers: through the builtin it
+    // is placed among the tile's accumulation registers, which the compiler then moves about in every
+    // K-step.  (Both operands E4M3; the result is next read a whole K-step later.)
+    auto ride_mfma = [&]() {
+        asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+v"(accx) : "v"(sb), "v"(xa));
+    };
+    if constexpr (TAIL == 3) ride_load(0, false);
+
     // The side job's first operand fetches go out ahead of the tile's first stage; the job itself
     // runs while that stage is in flight or has landed, and ends with a barrier, after which the
     // second stage may overwrite the ring slots it used.
@@ -590,6 +640,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     barrier_lds_only();
 #pragma unroll
     for (int f = 0; f < N_FRAG; ++f) read_frag(lds, lds_b, 0, f);
+    if constexpr (TAIL == 3) {
+        xa = ride_read(lds);
+        ride_mfma();
+        if (KT > 1) ride_load(1, false);
+    }
     __builtin_amdgcn_s_waitcnt(WAIT_LDS);
 
     int ia = 0;                                               // ring slot of stage kt's left tile
@@ -643,6 +698,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
 #pragma unroll
             for (int ni = 0; ni < NB; ++ni) {
                 const int q = mi * NB + ni;
+                if (TAIL == 3 && (STEADY || next)) {               // the adapter product's share of stage k+1
+                    if (q == N_FRAG) xa = ride_read(tA);           // behind the reads of the next half-step's operands
+                    if (q == N_FRAG + 4) {
+                        ride_mfma();
+                        if (STEADY || fetch) ride_load(kt + 2, STEADY);
+                    }
+                }
                 acc[mi][ni] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(
                     bf[1][ni], af[1][mi], acc[mi][ni], 0 /* E4M3 */, A_FMT, 0, 0, 0, 0);
                 if (STEADY || fast) {
@@ -665,6 +727,21 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     for (; kt < steady_steps; ++kt) k_step(kt, std::true_type{});
     for (; kt < KT; ++kt) k_step(kt, std::false_type{});
     __builtin_amdgcn_s_waitcnt(WAIT_ALL);
+    if constexpr (TAIL == 3) {
+        // lane l holds token row l % 16 of the block and ranks [4 (l / 16), +4)
+        const int r = static_cast<int>(tail->r);
+        const int64_t row = m0 + (ride_u & 15) * 16 + (lane & 15);
+        const int col = ride_rank0 + (lane >> 4) * 4;
+        if (row < M && col < r) {
+            uint2 pk;
+            pk.x = pack_bf16x2(accx[0] * inv, accx[1] * inv);
+            pk.y = pack_bf16x2(accx[2] * inv, accx[3] * inv);
+            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(g.c1) + row * g.ldc1 + col) = pk;
+            ride_max = fmaxf(fmaxf(fabsf(__uint_as_float(pk.x << 16)), fabsf(__uint_as_float(pk.x & 0xffff0000u))),
+                             fmaxf(fabsf(__uint_as_float(pk.y << 16)), fabsf(__uint_as_float(pk.y & 0xffff0000u))));
+        }
+        for (int off = 32; off > 0; off >>= 1) ride_max = fmaxf(ride_max, __shfl_xor(ride_max, off, 64));
+    }
 
     // ---- epilogue: rescale, convert, stage through LDS, split, store ----------------------------
     // Accumulator layout of a 32x32 block (weight operand first): lane l holds token row l % 32;
@@ -673,6 +750,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     // WM*32 rows out with 16 bytes per lane, row-contiguous.
     float oa_max = 0.0f;
     __syncthreads();                                              // all operand reads are done
+    // the waves' maxima of |O_A| meet in the last bytes of the rings, beyond the staging rows
+    float* const ride_max_slot = reinterpret_cast<float*>(lds + gemm_lds_bytes<WM, WN, MB, NB>() - 64);
+    if constexpr (TAIL == 3) {
+        if (lane == 0) ride_max_slot[wave] = ride_max;
+    }
     // the output type is a run-time argument; each of the two bodies is compiled with it fixed
     auto epilogue = [&](auto is_f32) {
         constexpr bool F32 = decltype(is_f32)::value;
@@ -745,6 +827,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     };
     if (g.c0_is_f32) epilogue(std::true_type{});
     else epilogue(std::false_type{});
+    if constexpr (TAIL == 3) {                                    // (the epilogue ends with a barrier)
+        if (g.amax1 && threadIdx.x == 0) {
+            float mx = ride_max_slot[0];
+            for (int w = 1; w < NW; ++w) mx = fmaxf(mx, ride_max_slot[w]);
+            if (mx > 0.0f) atomicMax(g.amax1, __float_as_uint(mx));
+        }
+    }
     if (g.amax1 && n0 + BN > g.n_split) {
         for (int off = 32; off > 0; off >>= 1) oa_max = fmaxf(oa_max, __shfl_xor(oa_max, off, 64));
         // non-negative floats order like their bit patterns
@@ -766,6 +855,15 @@ gemm_fwd_tail_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, con
 {
     __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
     gemm_tile<2, 2, 4, 4, false, 0, 1>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
+}
+
+// The same product with the adapter product riding on the K-steps of the tiles themselves: writes
+// O_A (bf16) and its running maximum, no partial results.
+__global__ void __launch_bounds__(256)
+gemm_fwd_ride_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk, const TailArgs t)
+{
+    __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
+    gemm_tile<2, 2, 4, 4, false, 0, 3>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
 }
 
 __global__ void __launch_bounds__(256)
@@ -861,17 +959,28 @@ hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_
     return hipGetLastError();
 }
 
-// ---- tiles with side jobs: plans and launches ---------------------------------------------------
-// Forward: the tile columns of a tile row in sets of two (one where a tile row has a single tile),
-// one K slice per set, at most 8 slices, each a whole number of K-steps and none empty.  Used when
-// the rank fits the side job's LDS chunk and a slice is at most four chunks (beyond that the exposed
-// fetch round trips outweigh the saved round of tiles).
+// ---- tiles that also work for the adapter: plans and launches ------------------------------------
+// Forward.  Where a tile row has a wave for every 16x16 block of its O_A (four waves per tile
+// column, 16 r / 16 blocks), the blocks ride on the tiles' own K-steps and the launch writes O_A
+// itself (splits = 0, row_parts = 0: no partials, no sum pass).  Otherwise, for ranks up to 64, the
+// side job: the tile columns of a tile row in sets of two (one where a tile row has a single tile),
+// one K slice per set, at most 8 slices, each a whole number of K-steps and none empty; used when a
+// slice is at most four chunks (beyond that the exposed fetch round trips outweigh the saved round
+// of tiles).
 OaTailPlan plan_oa_tail(int64_t T, int64_t n, int64_t m, int64_t r)
 {
     OaTailPlan p{false, 0, 0, 1};
-    if (!use_big_tiles(T, m) || r > 64) return p;
+    if (!use_big_tiles(T, m)) return p;
     const int tiles_n = static_cast<int>((m + 255) / 256);
     const int KT = static_cast<int>((n + BK - 1) / BK);
+    if (4 * tiles_n >= 16 * static_cast<int>((r + 15) / 16)) {   // every 16x16 block of a tile row finds a wave
+        p.use = true;
+        p.splits = 0;
+        p.steps_per_split = 0;
+        p.row_parts = 0;
+        return p;
+    }
+    if (r > 64) return p;
     p.row_parts = tiles_n >= 2 ? 2 : 1;
     int s0 = tiles_n / p.row_parts < 8 ? tiles_n / p.row_parts : 8;
     if (s0 > KT) s0 = KT;
@@ -900,7 +1009,10 @@ hipError_t launch_gemm_fwd_tail(const GemmArgs& g, const TailArgs& t, hipStream_
 {
     const int tiles_m = static_cast<int>((g.M + 255) / 256), tiles_n = static_cast<int>((g.N + 255) / 256);
     const int chunk = (tiles_m * tiles_n + 7) / 8;
-    gemm_fwd_tail_kernel<<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
+    if (t.row_parts == 0)
+        gemm_fwd_ride_kernel<<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
+    else
+        gemm_fwd_tail_kernel<<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
     return hipGetLastError();
 }
 
