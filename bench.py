@@ -38,7 +38,7 @@ WARMUP_FLOOR_S = 0.3
 # rocprofv3 --pmc FETCH_SIZE (scaled by the plain-copy calibration) + WRITE_SIZE runs of this command;
 # the figures and the commands are in the committed summary named below.
 TRAFFIC_SOURCE = "profiles/bench_config2_pmc_hbm_traffic_and_mfma.md"
-TRAFFIC_BYTES = {"gemm_fwd_tail_kernel": 158.1e6, "gemm_dx_tail_kernel": 157.6e6}
+TRAFFIC_BYTES = {"gemm_fwd_ride_kernel": 158.1e6, "gemm_dx_tail_kernel": 157.6e6}
 
 
 def _events(fn, iters):
@@ -535,13 +535,13 @@ def main():
     # The dominant kernel of the step: the forward product launch (the backward one takes about as long).
     dominant_fwd = ms_prod_fwd >= ms_prod_bwd
     dom_ms, dom_flops = (ms_prod_fwd, flops_fwd) if dominant_fwd else (ms_prod_bwd, flops_bwd)
-    traffic = TRAFFIC_BYTES["gemm_fwd_tail_kernel" if dominant_fwd else "gemm_dx_tail_kernel"]
+    traffic = TRAFFIC_BYTES["gemm_fwd_ride_kernel" if dominant_fwd else "gemm_dx_tail_kernel"]
     roofline = {
         "bound": "mfma",
-        "kernel": ("gemm_fwd_tail_kernel (the product launch of falqon_melded_fwd: 256 tiles of 256x256 of X~ W~^T, each "
-                   "followed by its share of O_A)") if dominant_fwd else
+        "kernel": ("gemm_fwd_ride_kernel (the product launch of falqon_melded_fwd: 256 tiles of 256x256 of X~ W~^T, the "
+                   "blocks of O_A formed inside the tiles' own K-steps)") if dominant_fwd else
                   ("gemm_dx_tail_kernel (the product launch of falqon_melded_bwd: 256 tiles of 256x256 of dY~ W~, each "
-                   "followed by its share of dB)"),
+                   "preceded by its share of dB)"),
         "achieved": dom_flops / (dom_ms * 1e-3) / 1e12, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
         "frac": dom_flops / (dom_ms * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,
         "traffic": traffic, "traffic_source": TRAFFIC_SOURCE + " (rocprofv3 --pmc FETCH_SIZE x calibration + WRITE_SIZE of "
