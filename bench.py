@@ -38,7 +38,7 @@ WARMUP_FLOOR_S = 0.3
 # rocprofv3 --pmc FETCH_SIZE (scaled by the plain-copy calibration) + WRITE_SIZE runs of this command;
 # the figures and the commands are in the committed summary named below.
 TRAFFIC_SOURCE = "profiles/bench_config2_pmc_hbm_traffic_and_mfma.md"
-TRAFFIC_BYTES = {"gemm_fwd_ride_kernel": 158.1e6, "gemm_dx_tail_kernel": 157.6e6}
+TRAFFIC_BYTES = {"gemm_fwd_ride_kernel": 137.3e6, "gemm_dx_tail_kernel": 157.5e6}
 
 
 def _events(fn, iters):
@@ -353,8 +353,8 @@ def decoder_block(fq, args):
 
 def _product_launches(fq, layer, x, dy, cfg):
     """The two product launches of a step, each issued alone through falqon_fp8_gemm exactly as
-    falqon_melded_fwd / falqon_melded_bwd issue it (backbone product with the adapter's share as a
-    side job of its tiles), on the step's own operands.  Returns (forward fn, backward fn)."""
+    falqon_melded_fwd / falqon_melded_bwd issue it (backbone product whose workgroups also form the
+    adapter's product), on the step's own operands.  Returns (forward fn, backward fn)."""
     T, n, m, r = layer.T, layer.n, layer.m, layer.r
     layer.forward(x)
     layer.backward(dy, lr=cfg.lr)
