@@ -397,7 +397,7 @@ def layer_summary(fq, cfg_id, layer_index, steps, cpu_tokens, with_cpu):
     blocks = _wall_blocks(step, steps)
     ms = statistics.median(blocks)
     fwd, bwd = _product_launches(fq, layer, x, dy, cfg)
-    ms_f, ms_b = _median_events(fwd, max(20, steps // 4)), _median_events(bwd, max(20, steps // 4))
+    ms_f, ms_b = _median_events(fwd, max(100, steps // 4)), _median_events(bwd, max(100, steps // 4))
     fl_f, fl_b = 2.0 * T * n * (m + r), 2.0 * T * m * n + 2.0 * T * m * r
     out = {"workload": f"config {cfg_id} layer {layer_index} ({d['shape'].name}): T={T}, n={n}, m={m}, r={r}, k={k}; "
                        "fwd + bwd + proxy update per step",
@@ -474,7 +474,7 @@ def main():
     ms_graph = statistics.median(_wall_blocks(graph.replay, args.steps))
 
     # ---- per-call and per-kernel timing (HIP events on the launch stream) -------------------
-    it = max(20, args.steps)
+    it = max(500, args.steps)                      # launches per event-timed run, whatever K the step loop uses
     ms_fwd = _median_events(lambda: layer.forward(x), it)
     ms_bwd = _median_events(lambda: layer.backward(dy, lr=cfg.lr), it)
     # without clearing, so that the buffer keeps its content over the repeated calls (a cleared buffer ends up all
