@@ -184,7 +184,7 @@ def proxy_update_static(delta_buf, wq, m: int, r: int, k: int, idx_out, clear_se
 def fp8_gemm(a, a_fmt: int, b, b_is_kn: bool, s_a, s_b, c, side=None, side_ws=None) -> None:
     """C = A . op(B) / (s_a s_b): a [M,K] FP8; b E4M3 [N,K] or, with b_is_kn, [K,N].
     With `side` (adapter rows [r,K], or O_A codes [M,r] when b_is_kn) and a workspace it is the product
-    launch of the melded forward / backward call, adapter partials included."""
+    launch of the melded forward / backward call, the adapter's product (or its partial sums) included."""
     _dev(a, b, s_a, s_b, c, side, side_ws)
     M, K = a.shape
     N = b.shape[1] if b_is_kn else b.shape[0]
