@@ -335,15 +335,16 @@ constexpr int gemm_lds_bytes() { return (3 * WM * MB + 2 * WN * NB) * 32 * BK; }
 // modulo 8 is the XCD it runs on, `split` its K split; `lds` is gemm_lds_bytes() of LDS, 1 KB aligned.
 // TAIL selects what the workgroup does for the adapter besides its tile: 0 nothing; 1 a K slice of
 // the adapter product O_A as a side job ahead of the tile (forward); 2 a slice of the adapter
-// gradient dB as a side job ahead of the tile (input-gradient launch); 3 blocks of O_A formed inside
-// the tile's own K-steps, finished and written as bf16 with their maximum (forward).
+// gradient dB as a side job ahead of the tile (input-gradient launch); 3 and 4: blocks of O_A formed
+// inside the tile's own K-steps, one or two per wave, finished and written as bf16 with their maximum
+// (forward).
 template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT, int TAIL = 0>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, const int tiles_n, const int chunk,
                                           const int bid, const int split, uint8_t* const lds,
                                           const TailArgs* const tail = nullptr)
 {
     static_assert(TAIL == 0 || (WM == 2 && WN == 2 && MB == 4 && NB == 4), "side jobs ride on the 256x256 tile only");
-    static_assert((TAIL != 1 && TAIL != 3) || (!B_KN && A_FMT == 0), "the adapter product belongs to the forward product");
+    static_assert((TAIL != 1 && TAIL != 3 && TAIL != 4) || (!B_KN && A_FMT == 0), "the adapter product belongs to the forward product");
     static_assert(TAIL != 2 || (B_KN && A_FMT == 1), "the dB slice belongs to the input-gradient product");
     constexpr int BM = WM * MB * 32, BN = WN * NB * 32, NW = WM * WN;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
@@ -552,33 +553,46 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
         else if (f < N_FRAG) af[kh][f - NB] = read_a(sA, f - NB, kh);
     };
 
-    // ---- adapter product riding on the tile's own K-steps (TAIL == 3) ----------------------------
+    // ---- adapter product riding on the tile's own K-steps (TAIL == 3, 4) -------------------------
     // O_A of a tile row is 16 blocks of 16 token rows by r / 16 blocks of 16 ranks.  Wave w of tile
-    // column c takes block u = 4 c + w: token rows [16 (u % 16), +16) of the tile row, ranks
-    // [16 (u / 16), +16), over all of K.  Its token operand is read from the left tile that sits in
-    // LDS for the tile's own product, its adapter operand straight from memory one step ahead; one
-    // 16x16x128 MFMA per K-step and no partial results.  Waves without a block run the same
-    // instructions on clamped rows and store nothing, so the loop carries no branch for it.
-    v4f accx = {0.0f, 0.0f, 0.0f, 0.0f};
+    // column c takes, of token rows [16 (u % 16), +16) of the tile row, u = 4 c + w, the RB rank
+    // blocks from RB (u / 16) on (RB = 1 for TAIL == 3, 2 for TAIL == 4), over all of K.  Its token
+    // operand is read from the left tile that sits in LDS for the tile's own product, its adapter
+    // operands straight from memory one step ahead; RB 16x16x128 MFMAs per K-step and no partial
+    // results.  Waves without a block run the same instructions on clamped rows and store nothing, so
+    // the loop carries no branch for it.
+    constexpr bool RIDE = TAIL == 3 || TAIL == 4;
+    constexpr int RB = TAIL == 4 ? 2 : 1;
+    v4f accx[RB];
+#pragma unroll
+    for (int j = 0; j < RB; ++j) accx[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
     float ride_max = 0.0f;
-    v8i sb;
+    v8i sb[RB];
     const int ride_u = tile_n * NW + wave;
     const int ride_row = (ride_u & 15) * 16 + (lane & 15);     // row of the left tile
-    const int ride_rank0 = (ride_u >> 4) * 16;
-    // adapter operand of stage s; `inside`: the stage lies fully inside K (otherwise chunks beyond K are zeros)
+    const int ride_blk0 = (ride_u >> 4) * RB;                  // first rank block of the wave
+    // adapter operand of stage s: lane part of the address, and the wave's rank blocks (a block
+    // beyond the rank is clamped to the last one)
     const uint8_t* ride_src = nullptr;
-    if constexpr (TAIL == 3) {
-        const int r = static_cast<int>(tail->r);
-        const int row = ride_rank0 + (lane & 15);
-        ride_src = tail->side + static_cast<int64_t>(row < r ? row : r - 1) * g.ldb + (lane >> 4) * 32;
+    int64_t ride_off[RB];
+    if constexpr (RIDE) {
+        const int nblk = static_cast<int>(tail->r) / 16;
+        ride_src = tail->side + static_cast<int64_t>(lane & 15) * g.ldb + (lane >> 4) * 32;
+#pragma unroll
+        for (int j = 0; j < RB; ++j)
+            ride_off[j] = static_cast<int64_t>(ride_blk0 + j < nblk ? ride_blk0 + j : nblk - 1) * 16 * g.ldb;
     }
+    // `inside`: the stage lies fully inside K (otherwise chunks beyond K are zeros)
     auto ride_load = [&](int s, bool inside) {
-        const uint8_t* p = ride_src + static_cast<int64_t>(s) * BK;
         const int64_t gk = static_cast<int64_t>(s) * BK + (lane >> 4) * 32;
-        const v4i lo = *reinterpret_cast<const v4i*>(inside || gk < g.K ? p : g_zero16);
-        const v4i hi = *reinterpret_cast<const v4i*>(inside || gk + 16 < g.K ? p + 16 : g_zero16);
-        sb[0] = lo[0]; sb[1] = lo[1]; sb[2] = lo[2]; sb[3] = lo[3];
-        sb[4] = hi[0]; sb[5] = hi[1]; sb[6] = hi[2]; sb[7] = hi[3];
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const uint8_t* p = ride_src + ride_off[j] + static_cast<int64_t>(s) * BK;
+            const v4i lo = *reinterpret_cast<const v4i*>(inside || gk < g.K ? p : g_zero16);
+            const v4i hi = *reinterpret_cast<const v4i*>(inside || gk + 16 < g.K ? p + 16 : g_zero16);
+            sb[j][0] = lo[0]; sb[j][1] = lo[1]; sb[j][2] = lo[2]; sb[j][3] = lo[3];
+            sb[j][4] = hi[0]; sb[j][5] = hi[1]; sb[j][6] = hi[2]; sb[j][7] = hi[3];
+        }
     };
     auto ride_read = [&](const uint8_t* tile) -> v8i {         // lane l: row l % 16, K bytes [32 (l / 16), +32)
         const int cb = (lane >> 4) * 2;
@@ -596,9 +610,11 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     // is placed among the tile's accumulation registers, which the compiler then moves about in every
     // K-step.  (Both operands E4M3; the result is next read a whole K-step later.)
     auto ride_mfma = [&]() {
-        asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+v"(accx) : "v"(sb), "v"(xa));
+#pragma unroll
+        for (int j = 0; j < RB; ++j)
+            asm volatile("v_mfma_f32_16x16x128_f8f6f4 %0, %1, %2, %0" : "+v"(accx[j]) : "v"(sb[j]), "v"(xa));
     };
-    if constexpr (TAIL == 3) ride_load(0, false);
+    if constexpr (RIDE) ride_load(0, false);
 
     // The side job's first operand fetches go out ahead of the tile's first stage; the job itself
     // runs while that stage is in flight or has landed, and ends with a barrier, after which the
@@ -640,7 +656,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     barrier_lds_only();
 #pragma unroll
     for (int f = 0; f < N_FRAG; ++f) read_frag(lds, lds_b, 0, f);
-    if constexpr (TAIL == 3) {
+    if constexpr (RIDE) {
         xa = ride_read(lds);
         ride_mfma();
         if (KT > 1) ride_load(1, false);
@@ -698,7 +714,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
 #pragma unroll
             for (int ni = 0; ni < NB; ++ni) {
                 const int q = mi * NB + ni;
-                if (TAIL == 3 && (STEADY || next)) {               // the adapter product's share of stage k+1
+                if (RIDE && (STEADY || next)) {                    // the adapter product's share of stage k+1
                     if (q == N_FRAG) xa = ride_read(tA);           // behind the reads of the next half-step's operands
                     if (q == N_FRAG + 4) {
                         ride_mfma();
@@ -727,18 +743,22 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     for (; kt < steady_steps; ++kt) k_step(kt, std::true_type{});
     for (; kt < KT; ++kt) k_step(kt, std::false_type{});
     __builtin_amdgcn_s_waitcnt(WAIT_ALL);
-    if constexpr (TAIL == 3) {
+    if constexpr (RIDE) {
         // lane l holds token row l % 16 of the block and ranks [4 (l / 16), +4)
         const int r = static_cast<int>(tail->r);
         const int64_t row = m0 + (ride_u & 15) * 16 + (lane & 15);
-        const int col = ride_rank0 + (lane >> 4) * 4;
-        if (row < M && col < r) {
-            uint2 pk;
-            pk.x = pack_bf16x2(accx[0] * inv, accx[1] * inv);
-            pk.y = pack_bf16x2(accx[2] * inv, accx[3] * inv);
-            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(g.c1) + row * g.ldc1 + col) = pk;
-            ride_max = fmaxf(fmaxf(fabsf(__uint_as_float(pk.x << 16)), fabsf(__uint_as_float(pk.x & 0xffff0000u))),
-                             fmaxf(fabsf(__uint_as_float(pk.y << 16)), fabsf(__uint_as_float(pk.y & 0xffff0000u))));
+#pragma unroll
+        for (int j = 0; j < RB; ++j) {
+            const int col = (ride_blk0 + j) * 16 + (lane >> 4) * 4;
+            if (row < M && col < r) {
+                uint2 pk;
+                pk.x = pack_bf16x2(accx[j][0] * inv, accx[j][1] * inv);
+                pk.y = pack_bf16x2(accx[j][2] * inv, accx[j][3] * inv);
+                *reinterpret_cast<uint2*>(static_cast<uint16_t*>(g.c1) + row * g.ldc1 + col) = pk;
+                ride_max = fmaxf(ride_max,
+                                 fmaxf(fmaxf(fabsf(__uint_as_float(pk.x << 16)), fabsf(__uint_as_float(pk.x & 0xffff0000u))),
+                                       fmaxf(fabsf(__uint_as_float(pk.y << 16)), fabsf(__uint_as_float(pk.y & 0xffff0000u)))));
+            }
         }
         for (int off = 32; off > 0; off >>= 1) ride_max = fmaxf(ride_max, __shfl_xor(ride_max, off, 64));
     }
@@ -752,7 +772,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     __syncthreads();                                              // all operand reads are done
     // the waves' maxima of |O_A| meet in the last bytes of the rings, beyond the staging rows
     float* const ride_max_slot = reinterpret_cast<float*>(lds + gemm_lds_bytes<WM, WN, MB, NB>() - 64);
-    if constexpr (TAIL == 3) {
+    if constexpr (RIDE) {
         if (lane == 0) ride_max_slot[wave] = ride_max;
     }
     // the output type is a run-time argument; each of the two bodies is compiled with it fixed
@@ -827,7 +847,7 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     };
     if (g.c0_is_f32) epilogue(std::true_type{});
     else epilogue(std::false_type{});
-    if constexpr (TAIL == 3) {                                    // (the epilogue ends with a barrier)
+    if constexpr (RIDE) {                                         // (the epilogue ends with a barrier)
         if (g.amax1 && threadIdx.x == 0) {
             float mx = ride_max_slot[0];
             for (int w = 1; w < NW; ++w) mx = fmaxf(mx, ride_max_slot[w]);
@@ -859,11 +879,12 @@ gemm_fwd_tail_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, con
 
 // The same product with the adapter product riding on the K-steps of the tiles themselves: writes
 // O_A (bf16) and its running maximum, no partial results.
+template <int RB>
 __global__ void __launch_bounds__(256)
 gemm_fwd_ride_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk, const TailArgs t)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
-    gemm_tile<2, 2, 4, 4, false, 0, 3>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
+    gemm_tile<2, 2, 4, 4, false, 0, RB == 2 ? 4 : 3>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
 }
 
 __global__ void __launch_bounds__(256)
@@ -960,9 +981,10 @@ hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_
 }
 
 // ---- tiles that also work for the adapter: plans and launches ------------------------------------
-// Forward.  Where a tile row has a wave for every 16x16 block of its O_A (four waves per tile
-// column, 16 r / 16 blocks), the blocks ride on the tiles' own K-steps and the launch writes O_A
-// itself (splits = 0, row_parts = 0: no partials, no sum pass).  Otherwise, for ranks up to 64, the
+// Forward.  Where the waves of a tile row (four per tile column) can take the 16x16 blocks of its
+// O_A (16 r / 16 of them) at one or two blocks each, the blocks ride on the tiles' own K-steps and
+// the launch writes O_A itself (splits = 0, row_parts = 0, steps_per_split = blocks per wave: no
+// partials, no sum pass).  Otherwise, for ranks up to 64, the
 // side job: the tile columns of a tile row in sets of two (one where a tile row has a single tile),
 // one K slice per set, at most 8 slices, each a whole number of K-steps and none empty; used when a
 // slice is at most four chunks (beyond that the exposed fetch round trips outweigh the saved round
@@ -973,12 +995,14 @@ OaTailPlan plan_oa_tail(int64_t T, int64_t n, int64_t m, int64_t r)
     if (!use_big_tiles(T, m)) return p;
     const int tiles_n = static_cast<int>((m + 255) / 256);
     const int KT = static_cast<int>((n + BK - 1) / BK);
-    if (4 * tiles_n >= 16 * static_cast<int>((r + 15) / 16)) {   // every 16x16 block of a tile row finds a wave
-        p.use = true;
-        p.splits = 0;
-        p.steps_per_split = 0;
-        p.row_parts = 0;
-        return p;
+    for (int rb = 1; rb <= 2; ++rb) {
+        if (4 * tiles_n * rb >= 16 * static_cast<int>((r + 15) / 16)) {   // every 16x16 block of a tile row finds a wave
+            p.use = true;
+            p.splits = 0;
+            p.steps_per_split = rb;                                       // rank blocks per wave
+            p.row_parts = 0;
+            return p;
+        }
     }
     if (r > 64) return p;
     p.row_parts = tiles_n >= 2 ? 2 : 1;
@@ -1009,8 +1033,10 @@ hipError_t launch_gemm_fwd_tail(const GemmArgs& g, const TailArgs& t, hipStream_
 {
     const int tiles_m = static_cast<int>((g.M + 255) / 256), tiles_n = static_cast<int>((g.N + 255) / 256);
     const int chunk = (tiles_m * tiles_n + 7) / 8;
-    if (t.row_parts == 0)
-        gemm_fwd_ride_kernel<<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
+    if (t.row_parts == 0 && t.steps_per_split == 2)
+        gemm_fwd_ride_kernel<2><<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
+    else if (t.row_parts == 0)
+        gemm_fwd_ride_kernel<1><<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
     else
         gemm_fwd_tail_kernel<<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
     return hipGetLastError();

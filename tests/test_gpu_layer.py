@@ -111,6 +111,8 @@ def test_forward_exact_integer_case_is_bit_exact(T, n, m, r):
                                      (2400, 3344, 3568, 32),     # ... two rank blocks
                                      (2400, 1040, 3328, 48),     # ... three rank blocks, whole tile columns
                                      (1100, 640, 8400, 128),     # ... rank 128 on a wide layer
+                                     (2400, 3344, 4336, 128),    # ... rank 128, two rank blocks per wave
+                                     (1100, 400, 8400, 256),     # ... rank 256 on a wide layer, likewise
                                      (4096, 128, 4336, 64),      # ... a single K-step
                                      (2100, 272, 4352, 16)])     # ... three K-steps, the last one 16 wide
 def test_large_tile_paths_exact_integer_case_is_bit_exact(T, n, m, r):
