@@ -208,33 +208,39 @@ gram_kernel(const float* __restrict__ y, int l, int64_t m, double* __restrict__ 
 
 // Symmetric eigen-decomposition of H (l x l, l even, fp64) by two-sided Jacobi with the round-robin
 // ordering: each round rotates l/2 disjoint index pairs at once.  One workgroup; H lives in LDS,
-// the eigenvectors P (columns) in global memory.  Stops after the first sweep without a rotation, or
-// after `sweeps`.  On exit lambda[i] = H[i][i] and order[k] is the
+// the eigenvectors P (columns) beside it where both fit (P_IN_LDS, l <= 96: a round then touches no
+// memory), in global memory otherwise.  Stops after the first sweep without a rotation, or after
+// `sweeps`.  On exit lambda[i] = H[i][i] and order[k] is the
 // index of the k-th largest eigenvalue.
-__global__ void __launch_bounds__(kThreads)
+// 1024 threads: a round is three short LDS-bound phases between barriers, the more lanes the shorter
+constexpr int kJacobiThreads = 1024;
+
+template <bool P_IN_LDS>
+__global__ void __launch_bounds__(kJacobiThreads)
 jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p, double* __restrict__ lambda,
                   int* __restrict__ order, int sweeps)
 {
-    extern __shared__ double s_h[];                                   // [l][l], then c[l/2], s[l/2], pair[l]
-    double* const s_c = s_h + l * l;
+    extern __shared__ double s_h[];                                   // [l][l], (P [l][l],) then c[l/2], s[l/2], pairs
+    double* const s_p = P_IN_LDS ? s_h + l * l : p;                   // the eigenvectors while they are rotated
+    double* const s_c = s_h + (P_IN_LDS ? 2 : 1) * l * l;
     double* const s_s = s_c + l / 2;
-    int* const s_pos = reinterpret_cast<int*>(s_s + l / 2);           // round-robin positions [l]
-    int* const s_pp = s_pos + l;                                      // pairs of this round: p[k], q[k]
+    int* const s_pp = reinterpret_cast<int*>(s_s + l / 2);            // pairs of this round: p[k], q[k]
     int* const s_rot = s_pp + l;                                      // rotations taken in this sweep
-    for (int q = threadIdx.x; q < l * l; q += kThreads) {
+    for (int q = threadIdx.x; q < l * l; q += kJacobiThreads) {
         s_h[q] = h_in[q];
-        p[q] = (q / l == q % l) ? 1.0 : 0.0;
+        s_p[q] = (q / l == q % l) ? 1.0 : 0.0;
     }
-    for (int q = threadIdx.x; q < l; q += kThreads) s_pos[q] = q;
     __syncthreads();
     const int half = l / 2;
+    // round-robin ordering: position 0 keeps index 0, positions 1 .. l-1 rotate by one per round
+    auto at = [&](int pos, int round) { return pos == 0 ? 0 : (pos - 1 + (l - 1) - round % (l - 1)) % (l - 1) + 1; };
     for (int sweep = 0; sweep < sweeps; ++sweep) {
         if (threadIdx.x == 0) *s_rot = 0;
         __syncthreads();
         for (int round = 0; round < l - 1; ++round) {
-            // pairs (pos[k], pos[l-1-k]) and their rotations from the current 2x2 blocks
-            for (int k = threadIdx.x; k < half; k += kThreads) {
-                int a = s_pos[k], b = s_pos[l - 1 - k];
+            // pairs (positions k and l-1-k) and their rotations from the current 2x2 blocks
+            for (int k = threadIdx.x; k < half; k += kJacobiThreads) {
+                int a = at(k, round), b = at(l - 1 - k, round);
                 if (a > b) { const int t = a; a = b; b = t; }
                 s_pp[2 * k] = a; s_pp[2 * k + 1] = b;
                 const double haa = s_h[a * l + a], hbb = s_h[b * l + b], hab = s_h[a * l + b];
@@ -251,20 +257,20 @@ jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p
             }
             __syncthreads();
             // columns: H <- H J, P <- P J   (pairs are disjoint, so all of them at once)
-            for (int q = threadIdx.x; q < half * l; q += kThreads) {
+            for (int q = threadIdx.x; q < half * l; q += kJacobiThreads) {
                 const int k = q / l, i = q - k * l;
                 const int a = s_pp[2 * k], b = s_pp[2 * k + 1];
                 const double c = s_c[k], s = s_s[k];
                 const double ha = s_h[i * l + a], hb = s_h[i * l + b];
                 s_h[i * l + a] = c * ha - s * hb;
                 s_h[i * l + b] = s * ha + c * hb;
-                const double pa = p[i * l + a], pb = p[i * l + b];
-                p[i * l + a] = c * pa - s * pb;
-                p[i * l + b] = s * pa + c * pb;
+                const double pa = s_p[i * l + a], pb = s_p[i * l + b];
+                s_p[i * l + a] = c * pa - s * pb;
+                s_p[i * l + b] = s * pa + c * pb;
             }
             __syncthreads();
             // rows: H <- J^T H
-            for (int q = threadIdx.x; q < half * l; q += kThreads) {
+            for (int q = threadIdx.x; q < half * l; q += kJacobiThreads) {
                 const int k = q / l, j = q - k * l;
                 const int a = s_pp[2 * k], b = s_pp[2 * k + 1];
                 const double c = s_c[k], s = s_s[k];
@@ -273,21 +279,16 @@ jacobi_eig_kernel(const double* __restrict__ h_in, int l, double* __restrict__ p
                 s_h[b * l + j] = s * ha + c * hb;
             }
             __syncthreads();
-            // next round: position 0 stays, the others rotate by one
-            if (threadIdx.x == 0) {
-                const int last = s_pos[l - 1];
-                for (int q = l - 1; q > 1; --q) s_pos[q] = s_pos[q - 1];
-                s_pos[1] = last;
-            }
-            __syncthreads();
         }
         if (*s_rot == 0) break;                                       // converged (same value in every lane)
         __syncthreads();
     }
-    for (int i = threadIdx.x; i < l; i += kThreads) lambda[i] = s_h[i * l + i];
+    if (P_IN_LDS)
+        for (int q = threadIdx.x; q < l * l; q += kJacobiThreads) p[q] = s_p[q];
+    for (int i = threadIdx.x; i < l; i += kJacobiThreads) lambda[i] = s_h[i * l + i];
     __syncthreads();
     // rank by eigenvalue, larger first, equal values by smaller index
-    for (int i = threadIdx.x; i < l; i += kThreads) {
+    for (int i = threadIdx.x; i < l; i += kJacobiThreads) {
         const double li = s_h[i * l + i];
         int rank = 0;
         for (int j = 0; j < l; ++j) {
@@ -398,11 +399,17 @@ hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t
     FQ_CHECK_LAUNCH();
     gram_kernel<<<dim3(l, l), kThreads, 0, stream>>>(y, l, m, h);
     FQ_CHECK_LAUNCH();
-    const size_t lds = sizeof(double) * (static_cast<size_t>(l) * l + l) + sizeof(int) * (2 * static_cast<size_t>(l) + 4);
-    err = hipFuncSetAttribute(reinterpret_cast<const void*>(&jacobi_eig_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+    // H, and the eigenvectors too while both fit the LDS (l <= 96; rotated in memory otherwise)
+    const size_t mat = sizeof(double) * static_cast<size_t>(l) * l;
+    const size_t rest = sizeof(double) * static_cast<size_t>(l) + sizeof(int) * (static_cast<size_t>(l) + 4);
+    const bool p_in_lds = 2 * mat + rest <= 160 * 1024;
+    const size_t lds = (p_in_lds ? 2 : 1) * mat + rest;
+    const void* jacobi = p_in_lds ? reinterpret_cast<const void*>(&jacobi_eig_kernel<true>)
+                                  : reinterpret_cast<const void*>(&jacobi_eig_kernel<false>);
+    err = hipFuncSetAttribute(jacobi, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
     if (err != hipSuccess) return err;
-    jacobi_eig_kernel<<<1, kThreads, lds, stream>>>(h, l, p, lambda, order, 14);
+    if (p_in_lds) jacobi_eig_kernel<true><<<1, kJacobiThreads, lds, stream>>>(h, l, p, lambda, order, 14);
+    else jacobi_eig_kernel<false><<<1, kJacobiThreads, lds, stream>>>(h, l, p, lambda, order, 14);
     FQ_CHECK_LAUNCH();
     rotate_kernel<<<dim3(static_cast<unsigned>((n + kThreads - 1) / kThreads), static_cast<unsigned>(r)), kThreads, 0,
                     stream>>>(z, l, n, p, lambda, order, static_cast<int>(r), a_out, sigma_out, 0);
