@@ -607,12 +607,13 @@ def main():
 
     out = {
         "metric": METRIC, "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1,
-        "steps": args.steps, "warmup": warm_done, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "fp8 (E4M3 weights/activations, E5M2 gradients), fp32 accumulate",
         "data": "synthetic",
         "config": {"workload": f"config {cfg.cfg} ({cfg.name}): T={T}, n={n}, m={m}, r={r}, k={k}; "
                                "fwd + bwd + proxy update per step",
                    "launch": "call by call through the C ABI", "repeats": REPEATS,
+                   "warmup_steps_done": warm_done,      # W, or as many steps as the warm-up floor (seconds) takes
                    "ms_per_step_blocks": blocks},
         "roofline": roofline, "kernels": kernels, "context": context,
     }
