@@ -128,7 +128,7 @@ hipError_t launch_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t n, 
 // ---- initialization (init.hip) -----------------------------------------------------------------
 hipError_t launch_init_residual(const float* w, const uint8_t* wq, const float* s_w, int64_t count, float* e,
                                 hipStream_t stream);
-struct SvdLayout { size_t z, y, h, p, lambda, order, total; };   // offsets into the workspace, l = r + 8 vectors
+struct SvdLayout { size_t z, y, h, p, lambda, order, part, total; };   // offsets into the workspace, l = r + 8 vectors
 SvdLayout svd_layout(int64_t m, int64_t n, int64_t r);
 // bt_out (nullable): the left factor, transposed: B^ = U_r sqrt(S_r) as fp32 [r, m]
 hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t r, const float* omega, int iters,

@@ -3,15 +3,15 @@
 // and the right factor of its rank-r truncated SVD,  A^ = sqrt(S_r) V_r^T  (line 5), which the
 // caller then casts with the backbone's scale (line 6, falqon_quantize with scale_in).
 //
-// This runs once per layer, before training; it is off the hot path and written for clarity first.  The SVD is a randomized subspace iteration (the paper only says "SVD";
-// a truncated factor is all it needs):
+// This runs once per layer, before training; it is off the hot path.  The SVD is a randomized
+// subspace iteration (the paper only says "SVD"; a truncated factor is all it needs):
 //   Z0 = orth(Omega)                         l = r + 8 rows of length n, Omega Gaussian (caller's);
 //                                            orth = Cholesky QR applied twice
 //   repeat q times:  Y = orth(Z E^T);  Z = orth(Y E)
 //   Y = Z E^T;  H = Y Y^T (l x l, fp64);  H = P diag(lambda) P^T  (cyclic Jacobi, fp64)
 //   A^[i,:] = lambda_i^(1/4) * sum_c P[c,i] Z[c,:]      for the r largest lambda_i = sigma_i^2
-// Products with E accumulate in fp32; everything l x l (Gram matrices, Cholesky factors, the
-// eigenproblem) is fp64.
+// Products with E accumulate in fp32 (matrix cores, slices of the contraction added in order);
+// everything l x l (Gram matrices, Cholesky factors, the eigenproblem) is fp64.
 #include "falqon_internal.h"
 
 namespace falqon {
@@ -46,92 +46,125 @@ copy_kernel(const float* __restrict__ src, float* __restrict__ dst, int64_t coun
 }
 
 constexpr int kMaxL = 128;                 // vectors in the subspace (r + 8 <= 128)
-constexpr int kVecGroup = 32;              // vectors per workgroup in the two products (grid.y groups)
-constexpr int kPerThread = kVecGroup / 4;  // vectors per thread
+constexpr int kMaxSlices = 16;             // slices of the contracted dimension in the two products
 
-// Y[c][i] = sum_j E[i][j] Z[c][j]:  a workgroup owns 64 rows of E and 32 of the vectors
-// (blockIdx.y) and walks j in chunks of 32.  thread: row i = t % 64, vectors c0 + t / 64 + 4 u.
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+// The two products with E run on the fp32 matrix cores (v_mfma_f32_32x32x2_f32), operands loaded
+// straight from memory into the instruction's layout: lane t supplies row (t % 32) of its
+// operand and depth index (t / 32).  A contraction does not care in which order its terms are
+// taken as long as both operands agree, so depth index h of four consecutive instructions stands
+// for four consecutive memory elements 4 h .. 4 h + 3 of an eight-element step: one 16-byte load
+// per lane and operand where the operand is contiguous along the contracted dimension.
+// The accumulator of (first, second) operand holds, in lane t, column (t % 32) = the second
+// operand's row, and in register v the first operand's row 8 (v / 4) + 4 (t / 32) + v % 4.
+// One wave owns 32 rows (or columns) of E and all l <= 32 NBV vectors over one slice of the
+// contracted dimension; the slices' results are added in order by sum_slices_kernel.
+
+// part[s][c][i] = sum over columns j of slice s of Z[c][j] E[i][j]
+template <int NBV>
 __global__ void __launch_bounds__(kThreads)
 apply_e_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* __restrict__ z, int l,
-               float* __restrict__ y)
+               float* __restrict__ part, int64_t per_slice)
 {
-    __shared__ float s_e[64][33];
-    __shared__ float s_z[kVecGroup][33];
-    const int ti = threadIdx.x & 63, tg = threadIdx.x >> 6;
-    const int64_t i0 = static_cast<int64_t>(blockIdx.x) * 64;
-    const int c0 = blockIdx.y * kVecGroup;
-    float acc[kPerThread];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+    const int64_t i0 = (static_cast<int64_t>(blockIdx.x) * (kThreads / 64) + wave) * 32;
+    if (i0 >= m) return;                                             // (no barrier in this kernel)
+    const int64_t j_begin = static_cast<int64_t>(blockIdx.y) * per_slice;
+    const int64_t j_end = j_begin + per_slice < n ? j_begin + per_slice : n;
+    const int64_t row = i0 + (lane & 31);
+    const float* const erow = e + (row < m ? row : m - 1) * n;
+    v16f acc[NBV];
 #pragma unroll
-    for (int u = 0; u < kPerThread; ++u) acc[u] = 0.0f;
-    for (int64_t j0 = 0; j0 < n; j0 += 32) {
-        __syncthreads();
-        for (int q = threadIdx.x; q < 64 * 32; q += kThreads) {
-            const int row = q >> 5, col = q & 31;
-            const int64_t gi = i0 + row, gj = j0 + col;
-            s_e[row][col] = (gi < m && gj < n) ? e[gi * n + gj] : 0.0f;
-        }
-        for (int q = threadIdx.x; q < kVecGroup * 32; q += kThreads) {
-            const int c = q >> 5, col = q & 31;
-            const int64_t gj = j0 + col;
-            s_z[c][col] = (c0 + c < l && gj < n) ? z[static_cast<int64_t>(c0 + c) * n + gj] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll 4
-        for (int jj = 0; jj < 32; ++jj) {
-            const float ev = s_e[ti][jj];
+    for (int b = 0; b < NBV; ++b)
 #pragma unroll
-            for (int u = 0; u < kPerThread; ++u) acc[u] = fmaf(ev, s_z[tg + 4 * u][jj], acc[u]);
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
+    const float4 zero = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+
+    for (int64_t j0 = j_begin; j0 < j_end; j0 += 8) {
+        const int64_t jj = j0 + 4 * h;                               // n and per_slice are multiples of 4 and 8
+        const bool in = jj < j_end;
+        const float4 ev = (in && row < m) ? *reinterpret_cast<const float4*>(erow + jj) : zero;
+#pragma unroll
+        for (int b = 0; b < NBV; ++b) {
+            const int c = b * 32 + (lane & 31);
+            const float4 zv = (in && c < l) ? *reinterpret_cast<const float4*>(z + static_cast<int64_t>(c) * n + jj) : zero;
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(zv.x, ev.x, acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(zv.y, ev.y, acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(zv.z, ev.z, acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(zv.w, ev.w, acc[b], 0, 0, 0);
         }
     }
-    if (i0 + ti < m) {
+    if (row >= m) return;
+    float* const out = part + static_cast<int64_t>(blockIdx.y) * l * m;
 #pragma unroll
-        for (int u = 0; u < kPerThread; ++u) {
-            const int c = c0 + tg + 4 * u;
-            if (c < l) y[static_cast<int64_t>(c) * m + i0 + ti] = acc[u];
+    for (int b = 0; b < NBV; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int c = b * 32 + 8 * (v / 4) + 4 * h + v % 4;
+            if (c < l) out[static_cast<int64_t>(c) * m + row] = acc[b][v];
         }
-    }
 }
 
-// Z[c][j] = sum_i E[i][j] Y[c][i]:  a workgroup owns 64 columns of E and walks i in chunks of 32.
+// part[s][c][j] = sum over rows i of slice s of Y[c][i] E[i][j]
+template <int NBV>
 __global__ void __launch_bounds__(kThreads)
 apply_et_kernel(const float* __restrict__ e, int64_t m, int64_t n, const float* __restrict__ y, int l,
-                float* __restrict__ z)
+                float* __restrict__ part, int64_t per_slice)
 {
-    __shared__ float s_e[32][65];
-    __shared__ float s_y[kVecGroup][33];
-    const int tj = threadIdx.x & 63, tg = threadIdx.x >> 6;
-    const int64_t j0 = static_cast<int64_t>(blockIdx.x) * 64;
-    const int c0 = blockIdx.y * kVecGroup;
-    float acc[kPerThread];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+    const int64_t j0 = (static_cast<int64_t>(blockIdx.x) * (kThreads / 64) + wave) * 32;
+    if (j0 >= n) return;                                             // (no barrier in this kernel)
+    const int64_t i_begin = static_cast<int64_t>(blockIdx.y) * per_slice;
+    const int64_t i_end = i_begin + per_slice < m ? i_begin + per_slice : m;
+    const int64_t col = j0 + (lane & 31);
+    const float* const ecol = e + (col < n ? col : n - 1);
+    v16f acc[NBV];
 #pragma unroll
-    for (int u = 0; u < kPerThread; ++u) acc[u] = 0.0f;
-    for (int64_t i0 = 0; i0 < m; i0 += 32) {
-        __syncthreads();
-        for (int q = threadIdx.x; q < 32 * 64; q += kThreads) {
-            const int row = q >> 6, col = q & 63;
-            const int64_t gi = i0 + row, gj = j0 + col;
-            s_e[row][col] = (gi < m && gj < n) ? e[gi * n + gj] : 0.0f;
-        }
-        for (int q = threadIdx.x; q < kVecGroup * 32; q += kThreads) {
-            const int c = q >> 5, row = q & 31;
-            const int64_t gi = i0 + row;
-            s_y[c][row] = (c0 + c < l && gi < m) ? y[static_cast<int64_t>(c0 + c) * m + gi] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll 4
-        for (int ii = 0; ii < 32; ++ii) {
-            const float ev = s_e[ii][tj];
+    for (int b = 0; b < NBV; ++b)
 #pragma unroll
-            for (int u = 0; u < kPerThread; ++u) acc[u] = fmaf(ev, s_y[tg + 4 * u][ii], acc[u]);
+        for (int v = 0; v < 16; ++v) acc[b][v] = 0.0f;
+    const float4 zero = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+
+    for (int64_t i0 = i_begin; i0 < i_end; i0 += 8) {
+        const int64_t ii = i0 + 4 * h;                               // m and per_slice are multiples of 4 and 8
+        const bool in = ii < i_end;
+        float ev[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) ev[t] = (in && col < n) ? ecol[(ii + t) * n] : 0.0f;
+#pragma unroll
+        for (int b = 0; b < NBV; ++b) {
+            const int c = b * 32 + (lane & 31);
+            const float4 yv = (in && c < l) ? *reinterpret_cast<const float4*>(y + static_cast<int64_t>(c) * m + ii) : zero;
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(yv.x, ev[0], acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(yv.y, ev[1], acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(yv.z, ev[2], acc[b], 0, 0, 0);
+            acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(yv.w, ev[3], acc[b], 0, 0, 0);
         }
     }
-    if (j0 + tj < n) {
+    if (col >= n) return;
+    float* const out = part + static_cast<int64_t>(blockIdx.y) * l * n;
 #pragma unroll
-        for (int u = 0; u < kPerThread; ++u) {
-            const int c = c0 + tg + 4 * u;
-            if (c < l) z[static_cast<int64_t>(c) * n + j0 + tj] = acc[u];
+    for (int b = 0; b < NBV; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int c = b * 32 + 8 * (v / 4) + 4 * h + v % 4;
+            if (c < l) out[static_cast<int64_t>(c) * n + col] = acc[b][v];
         }
+}
+
+// out[i] = part[0][i] + part[1][i] + ... in that order
+__global__ void __launch_bounds__(kThreads)
+sum_slices_kernel(const float* __restrict__ part, int slices, int64_t count, float* __restrict__ out)
+{
+    const int64_t i = (static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x) * 4;
+    if (i >= count) return;                                          // count is a multiple of 4
+    float4 s = *reinterpret_cast<const float4*>(part + i);
+    for (int k = 1; k < slices; ++k) {
+        const float4 v = *reinterpret_cast<const float4*>(part + static_cast<int64_t>(k) * count + i);
+        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
+    *reinterpret_cast<float4*>(out + i) = s;
 }
 
 // Orthonormalisation of the l rows of V[l][len] by Cholesky QR, applied twice: G = V V^T (fp64,
@@ -345,6 +378,7 @@ SvdLayout svd_layout(int64_t m, int64_t n, int64_t r)
     L.p = off;      off = up(off + sizeof(double) * l * l);
     L.lambda = off; off = up(off + sizeof(double) * l);
     L.order = off;  off = up(off + sizeof(int) * l);
+    L.part = off;   off = up(off + sizeof(float) * kMaxSlices * l * static_cast<size_t>(m > n ? m : n));
     L.total = off;
     return L;
 }
@@ -377,8 +411,32 @@ hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t
     double* p = reinterpret_cast<double*>(ws + L.p);
     double* lambda = reinterpret_cast<double*>(ws + L.lambda);
     int* order = reinterpret_cast<int*>(ws + L.order);
-    const unsigned gm = static_cast<unsigned>((m + 63) / 64), gn = static_cast<unsigned>((n + 63) / 64);
-    const unsigned gv = static_cast<unsigned>((l + kVecGroup - 1) / kVecGroup);
+    float* part = reinterpret_cast<float*>(ws + L.part);
+    // Y[l][m] = Z E^T (transposed == false) or Z[l][n] = Y E: slices of the contracted dimension so that about
+    // 2048 waves stream E, then the ordered sum of the slices
+    auto product = [&](bool transposed, const float* vec, float* out) -> hipError_t {
+        const int64_t rows = transposed ? n : m, depth = transposed ? m : n;
+        const int64_t blocks = (rows + 31) / 32;
+        int64_t slices = 2048 / blocks;
+        if (slices < 1) slices = 1;
+        if (slices > kMaxSlices) slices = kMaxSlices;
+        int64_t per = ((depth + slices - 1) / slices + 7) / 8 * 8;
+        slices = (depth + per - 1) / per;
+        const dim3 grid(static_cast<unsigned>((blocks + kThreads / 64 - 1) / (kThreads / 64)), static_cast<unsigned>(slices));
+        float* dst = slices > 1 ? part : out;
+        const int nbv = (l + 31) / 32;
+#define FQ_PRODUCT(NBV)                                                                                   \
+        if (transposed) apply_et_kernel<NBV><<<grid, kThreads, 0, stream>>>(e, m, n, vec, l, dst, per);   \
+        else apply_e_kernel<NBV><<<grid, kThreads, 0, stream>>>(e, m, n, vec, l, dst, per)
+        if (nbv == 1) { FQ_PRODUCT(1); } else if (nbv == 2) { FQ_PRODUCT(2); } else if (nbv == 3) { FQ_PRODUCT(3); } else { FQ_PRODUCT(4); }
+#undef FQ_PRODUCT
+        hipError_t pe = hipGetLastError();
+        if (pe != hipSuccess || slices == 1) return pe;
+        const int64_t count = static_cast<int64_t>(l) * rows;          // a multiple of 4 (m and n are)
+        sum_slices_kernel<<<static_cast<unsigned>((count / 4 + kThreads - 1) / kThreads), kThreads, 0, stream>>>(
+            part, static_cast<int>(slices), count, out);
+        return hipGetLastError();
+    };
     hipError_t err;
 #define FQ_CHECK_LAUNCH() do { err = hipGetLastError(); if (err != hipSuccess) return err; } while (0)
     copy_kernel<<<1024, kThreads, 0, stream>>>(omega, z, static_cast<int64_t>(l) * n);
@@ -386,17 +444,17 @@ hipError_t launch_svd_right_factor(const float* e, int64_t m, int64_t n, int64_t
     err = orthonormalize_rows(z, l, n, h, p, stream);
     if (err != hipSuccess) return err;
     for (int it = 0; it < iters; ++it) {
-        apply_e_kernel<<<dim3(gm, gv), kThreads, 0, stream>>>(e, m, n, z, l, y);
-        FQ_CHECK_LAUNCH();
+        err = product(false, z, y);
+        if (err != hipSuccess) return err;
         err = orthonormalize_rows(y, l, m, h, p, stream);
         if (err != hipSuccess) return err;
-        apply_et_kernel<<<dim3(gn, gv), kThreads, 0, stream>>>(e, m, n, y, l, z);
-        FQ_CHECK_LAUNCH();
+        err = product(true, y, z);
+        if (err != hipSuccess) return err;
         err = orthonormalize_rows(z, l, n, h, p, stream);
         if (err != hipSuccess) return err;
     }
-    apply_e_kernel<<<dim3(gm, gv), kThreads, 0, stream>>>(e, m, n, z, l, y);
-    FQ_CHECK_LAUNCH();
+    err = product(false, z, y);
+    if (err != hipSuccess) return err;
     gram_kernel<<<dim3(l, l), kThreads, 0, stream>>>(y, l, m, h);
     FQ_CHECK_LAUNCH();
     // H, and the eigenvectors too while both fit the LDS (l <= 96; rotated in memory otherwise)
