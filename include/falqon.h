@@ -321,12 +321,12 @@ falqon_status falqon_adamw_delta(const float* d_b, float* exp_avg, float* exp_av
 /*
  * Initialization (the paper's initialization algorithm; once per layer, off the hot path):
  *
- *   line 3   W~, s_w <- Q(W)                   falqon_quantize
- *   line 4   E = DQ(W~) - W                    falqon_init_residual   (the sign the reformulation
- *                                              equation fixes: DQ(W~) = W + E, E ~ B^ A^)
- *   line 5   B^, A^ <- SVD(E, r)               falqon_svd_right_factor: A^ = sqrt(S_r) V_r^T; B^ is
- *                                              never needed (it is implicit in W~)
- *   line 6   A~ <- cast(A^ * s_w)              falqon_quantize with scale_in = s_w into rows [m, m+r)
+ *   W~, s_w <- Q(W)                   falqon_quantize
+ *   E = DQ(W~) - W                    falqon_init_residual   (the sign the reformulation
+ *                                     equation fixes: DQ(W~) = W + E, E ~ B^ A^)
+ *   B^, A^ <- SVD(E, r)               falqon_svd_right_factor: A^ = sqrt(S_r) V_r^T; B^ is
+ *                                     never needed (it is implicit in W~)
+ *   A~ <- cast(A^ * s_w)              falqon_quantize with scale_in = s_w into rows [m, m+r)
  *
  * falqon_init_residual: e[i,j] = fl32( fl32(value(wq[i,j]) / s_w) - w[i,j] ), fp32 [m, n].
  *

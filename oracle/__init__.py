@@ -230,7 +230,7 @@ def proxy_update(buf, wq, m: int, r: int, k: int, clear_selected: bool = True):
 
 
 def init_residual(w, wq, s_w) -> np.ndarray:
-    """E = DQ(W~) - W in fp32 (initialization algorithm, line 4, with the sign of the reformulation equation)."""
+    """E = DQ(W~) - W in fp32 (initialization algorithm, residual step, with the sign of the reformulation equation)."""
     wf = _c(w, np.float32)
     q = _c(wq, np.uint8)
     assert wf.shape == q.shape
@@ -267,14 +267,14 @@ def da(xq, s_x, g, rows=None) -> np.ndarray:
 
 def svd_factors(e, r: int):
     """Both factors of the rank-r truncated SVD of E by the library's full SVD in fp64 (initialization
-    algorithm, line 5): B = U_r sqrt(S_r) [m, r], A = sqrt(S_r) V_r^T [r, n], and all singular values."""
+    algorithm, decomposition step): B = U_r sqrt(S_r) [m, r], A = sqrt(S_r) V_r^T [r, n], and all singular values."""
     u, sv, vt = np.linalg.svd(np.asarray(e, np.float64), full_matrices=False)
     root = np.sqrt(sv[:r])
     return u[:, :r] * root[None, :], root[:, None] * vt[:r], sv
 
 
 def svd_right_factor(e, r: int):
-    """Rank-r truncated SVD of E (initialization algorithm, line 5) by the library's full SVD in fp64:
+    """Rank-r truncated SVD of E (initialization algorithm, decomposition step) by the library's full SVD in fp64:
     E ~ B A with B = U_r sqrt(S_r), A = sqrt(S_r) V_r^T.  Returns (A fp64 [r, n], S fp64 [min(m, n)])."""
     u, sv, vt = np.linalg.svd(np.asarray(e, np.float64), full_matrices=False)
     return np.sqrt(sv[:r])[:, None] * vt[:r], sv

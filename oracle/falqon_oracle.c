@@ -427,7 +427,7 @@ void orc_proxy_update(float* buf, uint8_t* wq, int64_t n, int64_t m, int64_t r, 
 }
 
 /* ------------------------------------------------------------------------- */
-/* Initialization, residual step (initialization algorithm, line 4; the       */
+/* Initialization, residual step (initialization algorithm; the               */
 /* reformulation equation fixes the sign): the quantization error the adapter */
 /* is read out of,                                                            */
 /*   E[i,j] = fl32( fl32( dec(wq[i,j]) / s_w ) - w[i,j] )  =  DQ(W~) - W      */

@@ -1,7 +1,7 @@
 // Initialization (the paper's initialization algorithm): the quantization residual
-//   E = DQ(W~) - W            (line 4, with the sign the reformulation equation fixes)
-// and the right factor of its rank-r truncated SVD,  A^ = sqrt(S_r) V_r^T  (line 5), which the
-// caller then casts with the backbone's scale (line 6, falqon_quantize with scale_in).
+//   E = DQ(W~) - W            (its residual step, with the sign the reformulation equation fixes)
+// and the right factor of its rank-r truncated SVD,  A^ = sqrt(S_r) V_r^T  (its decomposition step),
+// which the caller then casts with the backbone's scale (its last step, falqon_quantize with scale_in).
 //
 // This runs once per layer, before training; it is off the hot path.  The SVD is a randomized
 // subspace iteration (the paper only says "SVD"; a truncated factor is all it needs):

@@ -97,7 +97,7 @@ def test_factor_of_a_quantization_residual_and_the_layer_it_initializes():
     assert np.max(np.abs(gram - np.diag(sig))) <= 1e-4 * sig[0]
     ev = ref["e"].astype(np.float64) @ (a / np.sqrt(sig)[:, None]).T
     assert np.max(np.abs(np.linalg.norm(ev, axis=0) - sig)) <= 1e-4 * sig[0]
-    # line 6: the cast of A^ with the backbone's scale equals the oracle's cast of the same A^
+    # last step of the initialization: the cast of A^ with the backbone's scale equals the oracle's cast of the same A^
     a32 = torch.from_numpy(a.astype(np.float32)).cuda()
     s_tmp = torch.zeros(1, device="cuda")
     fq.quantize(a32, fq.E4M3, layer.wq[m:], s_tmp, layer.ws, scale_in=layer.s_w)
