@@ -218,7 +218,7 @@ falqon_status falqon_proxy_update_static(float* delta_buf, uint8_t* wq, int64_t 
  * also form the adapter's small product, into side_ws.
  *   b_is_kn = 0 (melded forward; a = x~ E4M3 [T, n], b = backbone rows [m, n]):
  *       side = adapter rows A~ [r, n] E4M3; x~ A~^T, finished (bf16) where every tile row has
- *       enough tile columns to share it out (8 ceil(m / 256) >= r), else fp32 partials over
+ *       enough tile columns to share it out (m > 768 and 16 ceil(m / 256) >= r), else fp32 partials over
  *       slices of K
  *   b_is_kn = 1 (melded backward; a = dy~ E5M2 [T, m], b = backbone rows [m, n]):
  *       side = O_A cast to E4M3 [T, r]; partials of dy~^T O_A~ over groups of tokens

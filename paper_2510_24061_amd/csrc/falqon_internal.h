@@ -66,7 +66,7 @@ hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_
 //                          splits > 0: partial[splits][M][r], rescaled; tile columns in sets of
 //                          row_parts: set s < splits covers K-steps [s * steps_per_split,
 //                          +steps_per_split), each member a part of the token rows.
-//                          splits = 0 (row_parts = 0, steps_per_split = rank blocks per wave, 1 or 2):
+//                          splits = 0 (row_parts = 0, steps_per_split = rank blocks per wave, 1, 2 or 4):
 //                          no partials; the launch writes O_A as bf16 to g.c1 (row stride g.ldc1) and
 //                          raises g.amax1 (if not null) to its maximum
 //   input-gradient launch: side = O_A codes [T][r] (E4M3, cast by the dy quantizer's cast pass);

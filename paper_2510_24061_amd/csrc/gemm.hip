@@ -335,16 +335,16 @@ constexpr int gemm_lds_bytes() { return (3 * WM * MB + 2 * WN * NB) * 32 * BK; }
 // modulo 8 is the XCD it runs on, `split` its K split; `lds` is gemm_lds_bytes() of LDS, 1 KB aligned.
 // TAIL selects what the workgroup does for the adapter besides its tile: 0 nothing; 1 a K slice of
 // the adapter product O_A as a side job ahead of the tile (forward); 2 a slice of the adapter
-// gradient dB as a side job ahead of the tile (input-gradient launch); 3 and 4: blocks of O_A formed
-// inside the tile's own K-steps, one or two per wave, finished and written as bf16 with their maximum
-// (forward).
+// gradient dB as a side job ahead of the tile (input-gradient launch); 3, 4, 5: blocks of O_A formed
+// inside the tile's own K-steps, one, two or four per wave, finished and written as bf16 with their
+// maximum (forward).
 template <int WM, int WN, int MB, int NB, bool B_KN, int A_FMT, int TAIL = 0>
 __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, const int tiles_n, const int chunk,
                                           const int bid, const int split, uint8_t* const lds,
                                           const TailArgs* const tail = nullptr)
 {
     static_assert(TAIL == 0 || (WM == 2 && WN == 2 && MB == 4 && NB == 4), "side jobs ride on the 256x256 tile only");
-    static_assert((TAIL != 1 && TAIL != 3 && TAIL != 4) || (!B_KN && A_FMT == 0), "the adapter product belongs to the forward product");
+    static_assert((TAIL != 1 && TAIL != 3 && TAIL != 4 && TAIL != 5) || (!B_KN && A_FMT == 0), "the adapter product belongs to the forward product");
     static_assert(TAIL != 2 || (B_KN && A_FMT == 1), "the dB slice belongs to the input-gradient product");
     constexpr int BM = WM * MB * 32, BN = WN * NB * 32, NW = WM * WN;
     constexpr int A_BYTES = BM * BK, B_BYTES = BN * BK;
@@ -556,13 +556,13 @@ __device__ __forceinline__ void gemm_tile(const GemmArgs& g, const int tiles_m, 
     // ---- adapter product riding on the tile's own K-steps (TAIL == 3, 4) -------------------------
     // O_A of a tile row is 16 blocks of 16 token rows by r / 16 blocks of 16 ranks.  Wave w of tile
     // column c takes, of token rows [16 (u % 16), +16) of the tile row, u = 4 c + w, the RB rank
-    // blocks from RB (u / 16) on (RB = 1 for TAIL == 3, 2 for TAIL == 4), over all of K.  Its token
+    // blocks from RB (u / 16) on (RB = 1, 2, 4 for TAIL == 3, 4, 5), over all of K.  Its token
     // operand is read from the left tile that sits in LDS for the tile's own product, its adapter
     // operands straight from memory one step ahead; RB 16x16x128 MFMAs per K-step and no partial
     // results.  Waves without a block run the same instructions on clamped rows and store nothing, so
     // the loop carries no branch for it.
-    constexpr bool RIDE = TAIL == 3 || TAIL == 4;
-    constexpr int RB = TAIL == 4 ? 2 : 1;
+    constexpr bool RIDE = TAIL == 3 || TAIL == 4 || TAIL == 5;
+    constexpr int RB = TAIL == 5 ? 4 : TAIL == 4 ? 2 : 1;
     v4f accx[RB];
 #pragma unroll
     for (int j = 0; j < RB; ++j) accx[j] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
@@ -884,7 +884,7 @@ __global__ void __launch_bounds__(256)
 gemm_fwd_ride_kernel(const GemmArgs g, const int tiles_m, const int tiles_n, const int chunk, const TailArgs t)
 {
     __shared__ __attribute__((aligned(1024))) uint8_t lds[gemm_lds_bytes<2, 2, 4, 4>()];
-    gemm_tile<2, 2, 4, 4, false, 0, RB == 2 ? 4 : 3>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
+    gemm_tile<2, 2, 4, 4, false, 0, RB == 4 ? 5 : RB == 2 ? 4 : 3>(g, tiles_m, tiles_n, chunk, blockIdx.x, 0, lds, &t);
 }
 
 __global__ void __launch_bounds__(256)
@@ -982,7 +982,7 @@ hipError_t launch_gemm_fwd_pair(const GemmArgs& g, const GemmArgs& h, hipStream_
 
 // ---- tiles that also work for the adapter: plans and launches ------------------------------------
 // Forward.  Where the waves of a tile row (four per tile column) can take the 16x16 blocks of its
-// O_A (16 r / 16 of them) at one or two blocks each, the blocks ride on the tiles' own K-steps and
+// O_A (16 r / 16 of them) at one, two or four blocks each, the blocks ride on the tiles' own K-steps and
 // the launch writes O_A itself (splits = 0, row_parts = 0, steps_per_split = blocks per wave: no
 // partials, no sum pass).  Otherwise, for ranks up to 64, the
 // side job: the tile columns of a tile row in sets of two (one where a tile row has a single tile),
@@ -995,8 +995,11 @@ OaTailPlan plan_oa_tail(int64_t T, int64_t n, int64_t m, int64_t r)
     if (!use_big_tiles(T, m)) return p;
     const int tiles_n = static_cast<int>((m + 255) / 256);
     const int KT = static_cast<int>((n + BK - 1) / BK);
-    for (int rb = 1; rb <= 2; ++rb) {
-        if (4 * tiles_n * rb >= 16 * static_cast<int>((r + 15) / 16)) {   // every 16x16 block of a tile row finds a wave
+    const int rank_blocks = static_cast<int>((r + 15) / 16);
+    for (int rb = 1; rb <= 4; rb *= 2) {
+        // wave u of a tile row takes token block u % 16 and the rank blocks from rb (u / 16) on: the
+        // 4 tiles_n waves must reach every token block for every group of rb rank blocks
+        if (4 * tiles_n >= 16 * ((rank_blocks + rb - 1) / rb)) {
             p.use = true;
             p.splits = 0;
             p.steps_per_split = rb;                                       // rank blocks per wave
@@ -1033,7 +1036,9 @@ hipError_t launch_gemm_fwd_tail(const GemmArgs& g, const TailArgs& t, hipStream_
 {
     const int tiles_m = static_cast<int>((g.M + 255) / 256), tiles_n = static_cast<int>((g.N + 255) / 256);
     const int chunk = (tiles_m * tiles_n + 7) / 8;
-    if (t.row_parts == 0 && t.steps_per_split == 2)
+    if (t.row_parts == 0 && t.steps_per_split == 4)
+        gemm_fwd_ride_kernel<4><<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
+    else if (t.row_parts == 0 && t.steps_per_split == 2)
         gemm_fwd_ride_kernel<2><<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);
     else if (t.row_parts == 0)
         gemm_fwd_ride_kernel<1><<<dim3(static_cast<unsigned>(8 * chunk)), dim3(256), 0, stream>>>(g, tiles_m, tiles_n, chunk, t);

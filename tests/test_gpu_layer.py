@@ -113,6 +113,9 @@ def test_forward_exact_integer_case_is_bit_exact(T, n, m, r):
                                      (1100, 640, 8400, 128),     # ... rank 128 on a wide layer
                                      (2400, 3344, 4336, 128),    # ... rank 128, two rank blocks per wave
                                      (1100, 400, 8400, 256),     # ... rank 256 on a wide layer, likewise
+                                     (2400, 1040, 4336, 256),    # ... rank 256, four rank blocks per wave
+                                     (4100, 256, 2048, 48),      # ... three rank blocks at two per wave (one wave's second is empty)
+                                     (16400, 256, 512, 16),      # two tile columns: too few waves for the token blocks, side job instead
                                      (4096, 128, 4336, 64),      # ... a single K-step
                                      (2100, 272, 4352, 16)])     # ... three K-steps, the last one 16 wide
 def test_large_tile_paths_exact_integer_case_is_bit_exact(T, n, m, r):
