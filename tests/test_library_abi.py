@@ -209,7 +209,7 @@ def test_fp8_gemm_argument_validation(L):
     assert g(side=ok, r=64, ws=None, wsb=big) == 5
     assert g(side=ok, r=64, ws=ok, wsb=big - 1) == 5
     assert g(side=ok, r=20, ws=ok, wsb=big) == 2                       # r not a multiple of 16
-    assert g(side=ok, r=128, ws=ok, wsb=1 << 40) == 2                   # ranks beyond the side job's reach
+    assert g(side=ok, r=256, ws=ok, wsb=1 << 40) == 2                   # a rank beyond what 14 tile columns can share out
     assert g(side=ok, r=64, ws=ok, wsb=big, M=64) == 2                  # a small product does not use this launch
     assert g(side=odd, r=64, ws=ok, wsb=big) == 3
     assert g(side=ok, r=64, ws=ok, wsb=big, kn=1, af=0) == 4            # input-gradient orientation takes E5M2
