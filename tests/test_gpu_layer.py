@@ -116,6 +116,12 @@ def test_forward_exact_integer_case_is_bit_exact(T, n, m, r):
                                      (2400, 1040, 4336, 256),    # ... rank 256, four rank blocks per wave
                                      (4100, 256, 2048, 48),      # ... three rank blocks at two per wave (one wave's second is empty)
                                      (16400, 256, 512, 16),      # two tile columns: too few waves for the token blocks, side job instead
+                                     (8200, 128, 1024, 16),      # four tile columns, one wave per token block
+                                     (8200, 128, 1024, 64),      # ... four rank blocks per wave
+                                     (8200, 128, 1024, 128),     # ... eight rank blocks: beyond the in-loop form, paired launch
+                                     (11000, 128, 768, 32),      # three tile columns: side job
+                                     (33000, 128, 256, 16),      # a single tile column
+                                     (8200, 128, 1280, 80),      # five rank blocks on five tile columns: paired launch
                                      (4096, 128, 4336, 64),      # ... a single K-step
                                      (2100, 272, 4352, 16)])     # ... three K-steps, the last one 16 wide
 def test_large_tile_paths_exact_integer_case_is_bit_exact(T, n, m, r):
