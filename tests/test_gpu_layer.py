@@ -127,6 +127,32 @@ def test_forward_exact_integer_case_is_bit_exact(T, n, m, r):
 def test_large_tile_paths_exact_integer_case_is_bit_exact(T, n, m, r):
     """The exact-integer case at sizes that take the launches the benchmark times (256x256 backbone
     tiles together with the adapter's products): forward and backward, fp32 outputs bit for bit."""
+    _exact_integer_layer(T, n, m, r)
+
+
+def _large_tile_shapes(count, seed):
+    """Seeded shapes that take the 256x256 tiles (at least 128 of them) with every kind of tail, over
+    the whole range of tile columns and ranks; sized so that the fp64 reference takes about a second."""
+    g = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        m = int(g.integers(16, 330)) * 16
+        tiles_n = (m + 255) // 256
+        tiles_m = int(g.integers((128 + tiles_n - 1) // tiles_n, (128 + tiles_n - 1) // tiles_n + 6))
+        T = tiles_m * 256 - int(g.integers(0, 256))
+        n = int(g.integers(8, 65)) * 16
+        r = int(g.integers(1, 17)) * 16
+        if T * n * (m + r) <= 6e9 and r + 8 <= m:
+            out.append((T, n, m, r))
+    return out
+
+
+@pytest.mark.parametrize("shape", _large_tile_shapes(20, seed=24061))
+def test_random_large_tile_shapes_exact_integer_case_is_bit_exact(shape):
+    _exact_integer_layer(*shape)
+
+
+def _exact_integer_layer(T, n, m, r):
     g = np.random.default_rng(3)
     xi = g.integers(-4, 5, size=(T, n)).astype(np.float32)
     xi[5, 7] = 7.0                                   # s_x = 64
