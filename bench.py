@@ -625,9 +625,10 @@ def main():
             c1 = workloads.CONFIGS[1]
             out["cpu_baseline_config1"] = cpu_baseline(c1, workloads.config_layer_inputs(1), c1.T, 20)
     if not args.no_context and args.config == 2:
-        # the two MLP projections of the same model (config 3), time-capped
+        # the two MLP projections of the same model (config 3) and of the 13B block (config 4), time-capped
         sub_steps = max(20, min(200, args.steps))
         out["configs"] = [layer_summary(fq, 3, li, sub_steps, 1024, not args.no_cpu_baseline) for li in (0, 1)]
+        out["configs"] += [layer_summary(fq, 4, li, max(20, sub_steps // 2), 512, not args.no_cpu_baseline) for li in (1, 2)]
     print(json.dumps(out))
 
 
